@@ -1,0 +1,26 @@
+"""Compile the CPU oracle (plain C) into oracle/libqes_oracle.so.
+
+Test infrastructure: building the checker is not using it. The flags are part of the oracle's
+definition: -ffp-contract=off keeps gcc from fusing a*b+c on its own, so the only fused
+operations are the fmaf() calls written in the source.
+"""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "qes_oracle.c")
+LIB = os.path.join(HERE, "libqes_oracle.so")
+
+
+def build(force: bool = True) -> str:
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+        return LIB
+    cmd = ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-Wall", "-Wextra",
+           "-shared", "-fPIC", "-o", LIB, SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force="--if-stale" not in sys.argv))
