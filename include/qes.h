@@ -1,0 +1,190 @@
+/*
+ * libqes: the data-parallel hot path of Quantized Evolution Strategies (QES) on one MI355X.
+ *
+ * C ABI. Plain pointers and sizes only; every pointer is marked HOST or DEVICE. The library never
+ * takes ownership of caller memory. All device work is enqueued on the caller's stream
+ * (`stream` is a hipStream_t passed as void*; NULL is the default stream) and the calls return
+ * without waiting for it. Small HOST arrays (seeds, fitnesses) are copied before the call
+ * returns, so the caller may reuse them immediately.
+ *
+ * Every entry point returns QES_OK (0) or a negative qes_status; nothing throws. On error no
+ * device work has been enqueued.
+ *
+ * Passages of the paper each operation implements are cited at its declaration:
+ *   §3.2 Eq. 3  stochastically rounded integer perturbation δ
+ *   §3.2 Eq. 4  boundary gate (out-of-range perturbations are masked, not saturated)
+ *   §3.2 Eq. 5  discrete gradient estimate ĝ = 1/(Nσ) Σ_i F_i δ_i
+ *   §3.2 Eq. 6-8, Alg. 1  accumulated error feedback
+ *   §3.3, Alg. 2  stateless seed replay
+ *   App. A.1  weight formats, 4-bit δ container
+ * The noise generator (Philox4x32-10 -> Box-Muller -> stochastic rounding) is specified operation
+ * by operation in docs/NOISE_SPEC.md.
+ */
+#ifndef QES_H
+#define QES_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QES_OK = 0,
+    QES_ERR_INVALID_ARG = -1, /* null pointer, bad size, non-finite fitness, sigma out of range ... */
+    QES_ERR_UNSUPPORTED = -2, /* a legal request this build has no kernel for (stated per call)   */
+    QES_ERR_HIP = -3,         /* a HIP runtime call failed; qes_last_hip_error() has its code      */
+    QES_ERR_WORKSPACE = -4    /* workspace missing or smaller than qes_gemm_workspace_bytes()      */
+} qes_status;
+
+/* Limits of the small HOST arrays. */
+#define QES_MAX_POPULATION 1024 /* N */
+#define QES_MAX_HISTORY 256     /* hist_len */
+
+/*
+ * One quantised linear weight (App. A.1; INT4 group-scaled and INT8 per-output-channel formats).
+ *
+ *   qweight  DEVICE. Logical [out_features, in_features], row-major, in_features contiguous.
+ *            bits=4: two elements per byte; element 2b in the low nibble of byte b, element 2b+1 in
+ *            the high nibble; each nibble a 4-bit two's-complement integer.
+ *            bits=8: int8.
+ *            Must be 16-byte aligned. Updated IN PLACE by qes_update; read-only elsewhere.
+ *   scales   DEVICE, IEEE binary16. group_size>0: [out_features, in_features/group_size];
+ *            group_size==0: [out_features]. Read by qes_perturbed_qgemm only (may be NULL for
+ *            qes_update / qes_replay_residual: scales never enter the update).
+ *   qmin,qmax  the codebook range used by the gate: qmin <= value <= qmax.
+ *            bits=4: within [-8,7]; bits=8: within [-128,127].
+ *   tensor_id  caller-assigned, distinct per tensor; enters the Philox counter so that two
+ *            tensors never share noise.
+ * in_features must be even. out_features*in_features must be below 2^33 (the pair index is kept
+ * in 32 bits inside the tensor kernels).
+ */
+typedef struct {
+    void *qweight;
+    const void *scales;
+    int32_t out_features, in_features;
+    int32_t bits;       /* 4 or 8 */
+    int32_t group_size; /* bits=4: multiple of 32 dividing in_features; 0 = one scale per row */
+    int32_t qmin, qmax;
+    uint32_t tensor_id;
+} qes_tensor;
+
+/* ---- noise probes (docs/NOISE_SPEC.md; §3.2 Eq. 3). For tests and for callers that want δ. ---- */
+
+/*
+ * Raw Philox4x32-10 words of pairs [pair_begin, pair_begin+n_pairs): out4[j][0..3] for pair
+ * pair_begin+j, key = seed, counter = (pair lo, pair hi, tensor_id, 0).
+ * out4: DEVICE uint32 [n_pairs][4]. n_pairs == 0 is a no-op.
+ */
+int qes_noise_words(uint64_t seed, uint32_t tensor_id, uint64_t pair_begin, uint64_t n_pairs,
+                    uint32_t *out4, void *stream);
+
+/*
+ * The standard Gaussians ε of elements [elem_begin, elem_begin+n_elems) (element e uses pair e>>1,
+ * lane e&1). out: DEVICE float32 [n_elems].
+ */
+int qes_noise_gauss(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint64_t n_elems,
+                    float *out, void *stream);
+
+/*
+ * The integer perturbations δ (Eq. 3, clamped to the 4-bit container [-8,7]) of elements
+ * [elem_begin, elem_begin+n_elems). sigma >= 0 and finite. out: DEVICE int8 [n_elems].
+ */
+int qes_noise_delta(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint64_t n_elems,
+                    float sigma, int8_t *out, void *stream);
+
+/* ---- population evaluation (Alg. 1, steps "reconstruct δ_i", "W' = Gate(W_t+δ_i)", inference) ---- */
+
+/*
+ * Y[i,t,n] = Σ_g s[n,g] · Σ_{k in g} X[i,t,k] · W'_i[n,k] for every member i < N, where
+ * W'_i = Gate(W + δ_i) (Eq. 3, Eq. 4) is regenerated from seeds[i] inside the kernel and never
+ * stored.
+ *
+ *   seeds         HOST uint64 [N]
+ *   perturb_mask  HOST uint8 [N] or NULL (= all ones); 0 evaluates that member on the base weights
+ *   sigma         >= 0, finite; 0 evaluates every member on the base weights
+ *   x             DEVICE bfloat16 [N, T, in_features], 16-byte aligned
+ *   y             DEVICE bfloat16 [N, T, out_features] (written)
+ *   act_mode      0: bfloat16 activations; integer weights enter the MFMA as exact bfloat16 values
+ *                    and the scale is applied to fp32 partial sums at group boundaries.
+ *                 1: W8A8 (bits=8, group_size=0 only): symmetric dynamic per-token int8
+ *                    activations (a[t] = max|x|/127, 1 if that is 0), int8 MFMA with exact int32
+ *                    accumulation, Y = bf16(((float)acc·a[t])·s[n]).
+ *   workspace     DEVICE scratch of at least qes_gemm_workspace_bytes() bytes, 16-byte aligned
+ *                 (may be NULL when that is 0). Contents are overwritten.
+ *
+ * Requires in_features % 32 == 0, 1 <= N <= QES_MAX_POPULATION, T >= 1.
+ * QES_ERR_UNSUPPORTED: in_features not a multiple of 32, or group_size not a multiple of 32.
+ */
+int qes_perturbed_qgemm(const qes_tensor *w, const uint64_t *seeds, const uint8_t *perturb_mask,
+                        int32_t N, float sigma, const void *x, int32_t T, void *y, int32_t act_mode,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of DEVICE workspace qes_perturbed_qgemm needs for these arguments (0 for act_mode 0). */
+size_t qes_gemm_workspace_bytes(const qes_tensor *w, int32_t N, int32_t T, int32_t act_mode);
+
+/* ---- the seeded update (Alg. 2 whole; Eq. 5-8) ---- */
+
+/*
+ * Stateless QES update with seed replay, per element and in place:
+ *   c = α/(Nσ); e~ = 0
+ *   for τ = 0 .. hist_len-1 (oldest first):  g = Σ_i hist_fit[τ][i]·δ(hist_seeds[τ][i])
+ *        u = c·g + γ·e~;  Δ = Round(u);  Δf = Δ if qmin <= W_t+Δ <= qmax else 0;  e~ = u − Δf
+ *   g = Σ_i fit_t[i]·δ(seeds_t[i]);  u = c·g + γ·e~;  Δ = Round(u);  W_{t+1} = W_t+Δ if in range
+ * Every simulated step gates against the CURRENT weights W_t. Round is round-half-to-even; all
+ * residual arithmetic is fp32 in the fixed order given in docs/NOISE_SPEC.md and the oracle.
+ *
+ *   seeds_t, fit_t        HOST [N]; fit_t already normalised (see qes_normalize_fitness)
+ *   hist_seeds, hist_fit  HOST [hist_len][N], oldest generation first; NULL when hist_len == 0
+ *   hist_len              0 .. QES_MAX_HISTORY. 0 is the stateless deterministic-rounding update.
+ *   sigma > 0; alpha, gamma finite; every fitness finite.
+ *   stats                 DEVICE uint64 [2] or NULL. stats[0] += elements whose weight changed,
+ *                         stats[1] += elements whose non-zero Δ was masked by the gate (final
+ *                         step only). Accumulated with atomics; the caller zeroes it.
+ * The library owns no optimiser state: appending (seeds_t, fit_t) to the history is the caller's.
+ */
+int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
+               const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha,
+               float gamma, uint64_t *stats, void *stream);
+
+/*
+ * The replay loop of Alg. 2 alone: the proxy residual e~ after replaying the history, before the
+ * new population's step. residual: DEVICE float32 [out_features, in_features], 16-byte aligned.
+ * Weights are read, not written. Arguments as for qes_update.
+ */
+int qes_replay_residual(const qes_tensor *w, const uint64_t *hist_seeds, const float *hist_fit,
+                        int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
+                        float *residual, void *stream);
+
+/*
+ * Alg. 1 "normalize reward for population": z-score with the population standard deviation,
+ * computed in fp64; zero variance or N < 2 gives all zeros. HOST in, HOST out, no GPU work.
+ */
+int qes_normalize_fitness(const float *reward, int32_t N, float *fit);
+
+/* ---- machine ceilings measured with the library's own noise code (benchmark support) ---- */
+
+/*
+ * Runs `iters` Philox calls (mode 0) or full pair draws (mode 1: Philox + Box-Muller + two
+ * stochastic roundings) per thread on `n_threads` threads and xors the results into
+ * sink[n_threads] (DEVICE uint32) so the work cannot be elided. No memory traffic in the loop.
+ */
+int qes_bench_noise(int32_t mode, uint64_t n_threads, int32_t iters, float sigma, uint32_t *sink,
+                    void *stream);
+
+/* Plain streaming copy of n_bytes (multiple of 16) from src to dst, both DEVICE, 16-byte aligned. */
+int qes_bench_copy(const void *src, void *dst, size_t n_bytes, void *stream);
+
+/* ---- diagnostics ---- */
+
+const char *qes_status_string(int status);
+/* hipError_t of the last failing HIP call on this thread (0 if none). */
+int qes_last_hip_error(void);
+/* Library ABI version; bumped when a signature changes. */
+int qes_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QES_H */

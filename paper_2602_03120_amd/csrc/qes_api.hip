@@ -1,0 +1,345 @@
+// C ABI of libqes (declared in include/qes.h): argument validation, staging of the small host
+// arrays (seeds, fitnesses) into device memory in stream order, kernel launches.
+#include <cmath>
+#include <cstring>
+#include <mutex>
+
+#include "../../include/qes.h"
+#include "qes_internal.hpp"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    (void)hipGetLastError();   // clear the sticky error of a failed launch
+    return QES_ERR_HIP;
+}
+
+#define QES_HIP(expr)                                  \
+    do {                                               \
+        hipError_t e__ = (expr);                       \
+        if (e__ != hipSuccess) return hip_fail(e__);   \
+    } while (0)
+
+// ---- staging ring: host arrays -> pinned slot -> device slot, ordered on the caller's stream.
+// A slot is reused only after the event recorded behind its last consumer has completed.
+constexpr int kSlots = 8;
+constexpr int kMaxDevices = 16;
+
+struct Slot {
+    void *host = nullptr;
+    void *dev = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool in_flight = false;
+};
+
+struct DeviceCtx {
+    Slot slots[kSlots];
+    int next = 0;
+};
+
+std::mutex g_mu;
+DeviceCtx g_ctx[kMaxDevices];
+
+// Returns a slot holding `bytes` of capacity, safe to overwrite. Caller holds g_mu.
+int acquire_slot(size_t bytes, Slot **out)
+{
+    int dev = 0;
+    QES_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return QES_ERR_UNSUPPORTED;
+    DeviceCtx &c = g_ctx[dev];
+    Slot &s = c.slots[c.next];
+    c.next = (c.next + 1) % kSlots;
+    if (!s.ev) QES_HIP(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
+    if (s.in_flight) {
+        QES_HIP(hipEventSynchronize(s.ev));
+        s.in_flight = false;
+    }
+    if (s.cap < bytes) {
+        size_t cap = 1 << 16;
+        while (cap < bytes) cap <<= 1;
+        if (s.host) QES_HIP(hipHostFree(s.host));
+        if (s.dev) QES_HIP(hipFree(s.dev));
+        s.host = s.dev = nullptr;
+        s.cap = 0;
+        QES_HIP(hipHostMalloc(&s.host, cap, hipHostMallocDefault));
+        QES_HIP(hipMalloc(&s.dev, cap));
+        s.cap = cap;
+    }
+    *out = &s;
+    return QES_OK;
+}
+
+int tensor_check(const qes_tensor *w)
+{
+    if (!w || !w->qweight) return QES_ERR_INVALID_ARG;
+    if (w->out_features <= 0 || w->in_features <= 0 || (w->in_features & 1)) return QES_ERR_INVALID_ARG;
+    if (w->bits != 4 && w->bits != 8) return QES_ERR_INVALID_ARG;
+    if (w->group_size < 0) return QES_ERR_INVALID_ARG;
+    if (w->group_size > 0 && (w->in_features % w->group_size) != 0) return QES_ERR_INVALID_ARG;
+    if (w->qmin > w->qmax) return QES_ERR_INVALID_ARG;
+    if (w->bits == 4 && (w->qmin < -8 || w->qmax > 7)) return QES_ERR_INVALID_ARG;
+    if (w->bits == 8 && (w->qmin < -128 || w->qmax > 127)) return QES_ERR_INVALID_ARG;
+    if (((uintptr_t)w->qweight & 15u) != 0) return QES_ERR_INVALID_ARG;
+    if ((uint64_t)w->out_features * (uint64_t)w->in_features >= (1ull << 33)) return QES_ERR_UNSUPPORTED;
+    return QES_OK;
+}
+
+// Validates the update/replay scalars and fills the entry array (history first, current last).
+// Also bounds |u| so that the float -> int conversion in the kernel can never overflow.
+int fill_entries(qes::Entry *dst, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
+                 const float *hist_fit, int32_t hist_len, int32_t N, double c)
+{
+    double abs_sum = 0.0;
+    size_t o = 0;
+    for (int32_t tau = 0; tau < hist_len; ++tau)
+        for (int32_t i = 0; i < N; ++i, ++o) {
+            const float f = hist_fit[(size_t)tau * N + i];
+            if (!std::isfinite(f)) return QES_ERR_INVALID_ARG;
+            abs_sum += std::fabs((double)f);
+            const uint64_t s = hist_seeds[(size_t)tau * N + i];
+            uint32_t fb;
+            std::memcpy(&fb, &f, 4);
+            dst[o] = qes::Entry{(uint32_t)s, (uint32_t)(s >> 32), fb, 0u};
+        }
+    if (seeds_t) {
+        for (int32_t i = 0; i < N; ++i, ++o) {
+            const float f = fit_t[i];
+            if (!std::isfinite(f)) return QES_ERR_INVALID_ARG;
+            abs_sum += std::fabs((double)f);
+            uint32_t fb;
+            std::memcpy(&fb, &f, 4);
+            dst[o] = qes::Entry{(uint32_t)seeds_t[i], (uint32_t)(seeds_t[i] >> 32), fb, 0u};
+        }
+    }
+    // |δ| <= 8 and 0 <= γ <= 1, so |u| <= |c|·8·Σ|F| over every generation replayed
+    if (std::fabs(c) * 8.0 * abs_sum >= 1073741824.0) return QES_ERR_INVALID_ARG;
+    return QES_OK;
+}
+
+int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
+                  const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
+                  uint64_t *stats, float *residual, bool replay_only, void *stream)
+{
+    int rc = tensor_check(w);
+    if (rc != QES_OK) return rc;
+    if (N <= 0 || N > QES_MAX_POPULATION || hist_len < 0 || hist_len > QES_MAX_HISTORY) return QES_ERR_INVALID_ARG;
+    if (hist_len > 0 && (!hist_seeds || !hist_fit)) return QES_ERR_INVALID_ARG;
+    if (!replay_only && (!seeds_t || !fit_t)) return QES_ERR_INVALID_ARG;
+    if (replay_only && (!residual || ((uintptr_t)residual & 15u) != 0)) return QES_ERR_INVALID_ARG;
+    if (!(sigma > 0.0f) || !std::isfinite(sigma) || !std::isfinite(alpha)) return QES_ERR_INVALID_ARG;
+    if (!(gamma >= 0.0f && gamma <= 1.0f)) return QES_ERR_INVALID_ARG;
+    if (stats && ((uintptr_t)stats & 7u) != 0) return QES_ERR_INVALID_ARG;
+
+    const double c64 = (double)alpha / ((double)N * (double)sigma);
+    const int32_t steps = hist_len + (replay_only ? 0 : 1);
+    const size_t n_entries = (size_t)steps * (size_t)N;
+    hipStream_t s = (hipStream_t)stream;
+
+    qes::UpdateArgs a{};
+    a.qweight = w->qweight;
+    a.entries = nullptr;
+    a.residual = residual;
+    a.stats = (unsigned long long *)stats;
+    a.n_pairs = (uint32_t)(((uint64_t)w->out_features * (uint64_t)w->in_features) >> 1);
+    a.steps = steps;
+    a.N = N;
+    a.sigma = sigma;
+    a.c = (float)c64;
+    a.gamma = gamma;
+    a.qmin = w->qmin;
+    a.qspan = (uint32_t)(w->qmax - w->qmin);
+    a.tensor_id = w->tensor_id;
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    Slot *slot = nullptr;
+    if (n_entries > 0) {
+        rc = acquire_slot(n_entries * sizeof(qes::Entry), &slot);
+        if (rc != QES_OK) return rc;
+        rc = fill_entries((qes::Entry *)slot->host, replay_only ? nullptr : seeds_t, fit_t, hist_seeds, hist_fit,
+                          hist_len, N, c64);
+        if (rc != QES_OK) return rc;
+        QES_HIP(hipMemcpyAsync(slot->dev, slot->host, n_entries * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
+        a.entries = (const qes::Entry *)slot->dev;
+    }
+    hipError_t e = qes::launch_update(a, w->bits, replay_only, s);
+    if (slot) {
+        // the slot is busy until everything enqueued so far (copy and kernel) has run
+        hipError_t e2 = hipEventRecord(slot->ev, s);
+        if (e2 == hipSuccess) slot->in_flight = true;
+        else if (e == hipSuccess) e = e2;
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    return QES_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int qes_abi_version(void) { return 1; }
+
+int qes_last_hip_error(void) { return g_last_hip_error; }
+
+const char *qes_status_string(int status)
+{
+    switch (status) {
+    case QES_OK: return "ok";
+    case QES_ERR_INVALID_ARG: return "invalid argument";
+    case QES_ERR_UNSUPPORTED: return "unsupported configuration";
+    case QES_ERR_HIP: return "HIP runtime error";
+    case QES_ERR_WORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+    }
+}
+
+int qes_noise_words(uint64_t seed, uint32_t tensor_id, uint64_t pair_begin, uint64_t n_pairs, uint32_t *out4,
+                    void *stream)
+{
+    if (n_pairs == 0) return QES_OK;
+    if (!out4 || ((uintptr_t)out4 & 15u) != 0 || n_pairs > (1ull << 31)) return QES_ERR_INVALID_ARG;
+    if (pair_begin + n_pairs < pair_begin) return QES_ERR_INVALID_ARG;
+    QES_HIP(qes::launch_noise_words(seed, tensor_id, pair_begin, n_pairs, out4, (hipStream_t)stream));
+    return QES_OK;
+}
+
+int qes_noise_gauss(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint64_t n_elems, float *out,
+                    void *stream)
+{
+    if (n_elems == 0) return QES_OK;
+    if (!out || n_elems > (1ull << 31) || elem_begin + n_elems < elem_begin) return QES_ERR_INVALID_ARG;
+    QES_HIP(qes::launch_noise_gauss(seed, tensor_id, elem_begin, n_elems, out, (hipStream_t)stream));
+    return QES_OK;
+}
+
+int qes_noise_delta(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint64_t n_elems, float sigma,
+                    int8_t *out, void *stream)
+{
+    if (n_elems == 0) return QES_OK;
+    if (!out || n_elems > (1ull << 31) || elem_begin + n_elems < elem_begin) return QES_ERR_INVALID_ARG;
+    if (!(sigma >= 0.0f) || !std::isfinite(sigma)) return QES_ERR_INVALID_ARG;
+    QES_HIP(qes::launch_noise_delta(seed, tensor_id, elem_begin, n_elems, sigma, out, (hipStream_t)stream));
+    return QES_OK;
+}
+
+size_t qes_gemm_workspace_bytes(const qes_tensor *w, int32_t N, int32_t T, int32_t act_mode)
+{
+    if (!w || act_mode != 1 || N <= 0 || T <= 0) return 0;
+    const size_t rows = (size_t)N * (size_t)T;
+    const size_t xq = (rows * (size_t)w->in_features + 15u) & ~(size_t)15u;
+    return xq + rows * sizeof(float);
+}
+
+int qes_perturbed_qgemm(const qes_tensor *w, const uint64_t *seeds, const uint8_t *perturb_mask, int32_t N,
+                        float sigma, const void *x, int32_t T, void *y, int32_t act_mode, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    int rc = tensor_check(w);
+    if (rc != QES_OK) return rc;
+    if (!w->scales || !seeds || !x || !y || N <= 0 || N > QES_MAX_POPULATION || T <= 0) return QES_ERR_INVALID_ARG;
+    if (((uintptr_t)x & 15u) != 0 || ((uintptr_t)y & 1u) != 0 || ((uintptr_t)w->scales & 1u) != 0)
+        return QES_ERR_INVALID_ARG;
+    if (!(sigma >= 0.0f) || !std::isfinite(sigma)) return QES_ERR_INVALID_ARG;
+    if (act_mode != 0 && act_mode != 1) return QES_ERR_INVALID_ARG;
+    if (act_mode == 1 && (w->bits != 8 || w->group_size != 0)) return QES_ERR_INVALID_ARG;
+    if ((w->in_features % 32) != 0 || (w->group_size % 32) != 0) return QES_ERR_UNSUPPORTED;
+    if ((uint64_t)N * (uint64_t)T * (uint64_t)w->in_features >= (1ull << 40)) return QES_ERR_UNSUPPORTED;
+    hipStream_t s = (hipStream_t)stream;
+
+    qes::GemmArgs a{};
+    a.qweight = w->qweight;
+    a.scales = w->scales;
+    a.x = x;
+    a.x_scale = nullptr;
+    a.y = y;
+    a.out_features = w->out_features;
+    a.in_features = w->in_features;
+    a.group_size = w->group_size;
+    a.N = N;
+    a.T = T;
+    a.sigma = sigma;
+    a.qmin = w->qmin;
+    a.qspan = (uint32_t)(w->qmax - w->qmin);
+    a.tensor_id = w->tensor_id;
+
+    if (act_mode == 1) {
+        const size_t need = qes_gemm_workspace_bytes(w, N, T, act_mode);
+        if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15u) != 0) return QES_ERR_WORKSPACE;
+        const size_t rows = (size_t)N * (size_t)T;
+        int8_t *xq = (int8_t *)workspace;
+        float *xs = (float *)((char *)workspace + ((rows * (size_t)w->in_features + 15u) & ~(size_t)15u));
+        QES_HIP(qes::launch_quantize_activations(x, xq, xs, (int64_t)rows, w->in_features, s));
+        a.x = xq;
+        a.x_scale = xs;
+    }
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    Slot *slot = nullptr;
+    rc = acquire_slot((size_t)N * sizeof(qes::Entry), &slot);
+    if (rc != QES_OK) return rc;
+    qes::Entry *ent = (qes::Entry *)slot->host;
+    for (int32_t i = 0; i < N; ++i)
+        ent[i] = qes::Entry{(uint32_t)seeds[i], (uint32_t)(seeds[i] >> 32),
+                            (perturb_mask == nullptr || perturb_mask[i] != 0) ? 1u : 0u, 0u};
+    QES_HIP(hipMemcpyAsync(slot->dev, slot->host, (size_t)N * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
+    a.entries = (const qes::Entry *)slot->dev;
+    hipError_t e = qes::launch_gemm(a, w->bits, act_mode, s);
+    hipError_t e2 = hipEventRecord(slot->ev, s);
+    if (e2 == hipSuccess) slot->in_flight = true;
+    else if (e == hipSuccess) e = e2;
+    if (e != hipSuccess) return hip_fail(e);
+    return QES_OK;
+}
+
+int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
+               const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
+               uint64_t *stats, void *stream)
+{
+    return update_common(w, seeds_t, fit_t, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, stats, nullptr,
+                         false, stream);
+}
+
+int qes_replay_residual(const qes_tensor *w, const uint64_t *hist_seeds, const float *hist_fit, int32_t hist_len,
+                        int32_t N, float sigma, float alpha, float gamma, float *residual, void *stream)
+{
+    return update_common(w, nullptr, nullptr, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, nullptr,
+                         residual, true, stream);
+}
+
+int qes_normalize_fitness(const float *reward, int32_t N, float *fit)
+{
+    if (!reward || !fit || N <= 0) return QES_ERR_INVALID_ARG;
+    double mu = 0.0;
+    for (int32_t i = 0; i < N; ++i) mu += (double)reward[i];
+    mu /= (double)N;
+    double var = 0.0;
+    for (int32_t i = 0; i < N; ++i) {
+        const double d = (double)reward[i] - mu;
+        var += d * d;
+    }
+    const double sd = std::sqrt(var / (double)N);
+    for (int32_t i = 0; i < N; ++i) fit[i] = (N < 2 || sd == 0.0) ? 0.0f : (float)(((double)reward[i] - mu) / sd);
+    return QES_OK;
+}
+
+int qes_bench_noise(int32_t mode, uint64_t n_threads, int32_t iters, float sigma, uint32_t *sink, void *stream)
+{
+    if ((mode != 0 && mode != 1) || !sink || n_threads == 0 || n_threads > (1ull << 31) || iters < 0)
+        return QES_ERR_INVALID_ARG;
+    QES_HIP(qes::launch_bench_noise(mode, n_threads, iters, sigma, sink, (hipStream_t)stream));
+    return QES_OK;
+}
+
+int qes_bench_copy(const void *src, void *dst, size_t n_bytes, void *stream)
+{
+    if (!src || !dst || (n_bytes & 15u) != 0 || ((uintptr_t)src & 15u) != 0 || ((uintptr_t)dst & 15u) != 0)
+        return QES_ERR_INVALID_ARG;
+    QES_HIP(qes::launch_bench_copy(src, dst, n_bytes, (hipStream_t)stream));
+    return QES_OK;
+}
+
+}  // extern "C"

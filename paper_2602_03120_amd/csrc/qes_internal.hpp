@@ -1,0 +1,63 @@
+// Host-side declarations shared by the translation units of libqes (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace qes {
+
+// One (seed, fitness) record as the kernels read it: 16 bytes, one scalar load.
+struct Entry {
+    uint32_t seed_lo, seed_hi;
+    uint32_t fit_bits;   // float bits (update/replay) or perturb flag (GEMM)
+    uint32_t pad;
+};
+
+struct UpdateArgs {
+    void *qweight;
+    const Entry *entries;        // [steps][N], oldest generation first, current step last
+    float *residual;             // replay only
+    unsigned long long *stats;   // update only, may be null
+    uint32_t n_pairs;            // out*in/2
+    int32_t steps;               // generations to run (hist_len for replay, hist_len+1 for update)
+    int32_t N;
+    float sigma, c, gamma;
+    int32_t qmin;
+    uint32_t qspan;              // qmax - qmin
+    uint32_t tensor_id;
+};
+
+struct GemmArgs {
+    const void *qweight;
+    const void *scales;          // fp16
+    const Entry *entries;        // [N]: seed + perturb flag
+    const void *x;               // bf16 [N,T,in] (act_mode 0) or int8 [N,T,in] (act_mode 1)
+    const float *x_scale;        // act_mode 1: [N,T]
+    void *y;                     // bf16 [N,T,out]
+    int32_t out_features, in_features, group_size;
+    int32_t N, T;
+    float sigma;
+    int32_t qmin;
+    uint32_t qspan;
+    uint32_t tensor_id;
+};
+
+hipError_t launch_noise_words(uint64_t seed, uint32_t tensor_id, uint64_t pair_begin, uint64_t n_pairs,
+                              uint32_t *out4, hipStream_t s);
+hipError_t launch_noise_gauss(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint64_t n,
+                              float *out, hipStream_t s);
+hipError_t launch_noise_delta(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint64_t n,
+                              float sigma, int8_t *out, hipStream_t s);
+hipError_t launch_bench_noise(int mode, uint64_t n_threads, int iters, float sigma, uint32_t *sink,
+                              hipStream_t s);
+hipError_t launch_bench_copy(const void *src, void *dst, size_t n_bytes, hipStream_t s);
+
+// bits: 4|8; residual: write fp32 residual instead of updating the weights
+hipError_t launch_update(const UpdateArgs &a, int bits, bool residual, hipStream_t s);
+
+hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_scale, int64_t rows,
+                                       int32_t in_features, hipStream_t s);
+// returns hipErrorInvalidValue when no kernel covers the request
+hipError_t launch_gemm(const GemmArgs &a, int bits, int act_mode, hipStream_t s);
+
+}  // namespace qes

@@ -1,0 +1,122 @@
+// Device-side noise generator of the QES hot path for gfx950.
+//
+// Implements docs/NOISE_SPEC.md (paper §3.2 Eq. 3; App. A.1 for the 4-bit container):
+// Philox4x32-10 -> exactly specified Box-Muller -> stochastic rounding. Every floating-point
+// operation that can reach an integer is written out (explicit fma, no contraction: this file is
+// compiled with -ffp-contract=off), so the integers match the CPU oracle bit for bit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qes {
+
+constexpr uint32_t kPhiloxM0 = 0xD2511F53u;
+constexpr uint32_t kPhiloxM1 = 0xCD9E8D57u;
+constexpr uint32_t kPhiloxW0 = 0x9E3779B9u;
+constexpr uint32_t kPhiloxW1 = 0xBB67AE85u;
+
+struct Words {
+    uint32_t w0, w1, w2, w3;
+};
+
+// N1. Ten rounds on counter (c0,c1,c2,c3) with key (k0,k1). Arguments that are wave-uniform
+// (key, tensor id, high counter words) stay in scalar registers; the first rounds then cost less.
+__device__ __forceinline__ Words philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)kPhiloxM0 * (uint64_t)c0;
+        const uint64_t p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += kPhiloxW0;
+        k1 += kPhiloxW1;
+    }
+    return Words{c0, c1, c2, c3};
+}
+
+// N4. ln(m * 2^-24) for integer m in [1, 2^24]; result <= 0.
+__device__ __forceinline__ float ln_u1(uint32_t m)
+{
+    const float xf = (float)m;
+    const uint32_t ix = __float_as_uint(xf) - 0x3F3504F3u;
+    const int32_t e = (int32_t)(ix >> 23) - 24;
+    const float t = __uint_as_float((ix & 0x007FFFFFu) + 0x3F3504F3u) - 1.0f;
+    float p = -0x1.a7d988p-4f;
+    p = __builtin_fmaf(p, t, 0x1.4d64acp-3f);
+    p = __builtin_fmaf(p, t, -0x1.6049d0p-3f);
+    p = __builtin_fmaf(p, t, 0x1.976dd8p-3f);
+    p = __builtin_fmaf(p, t, -0x1.ff7476p-3f);
+    p = __builtin_fmaf(p, t, 0x1.5559f0p-2f);
+    p = __builtin_fmaf(p, t, -0x1.000060p-1f);
+    const float l1 = __builtin_fmaf(t * t, p, t);
+    return __builtin_fmaf((float)e, 0x1.62e430p-1f, l1);
+}
+
+// N3 + N4. The two standard Gaussians of one Philox call (lane 0: even element, lane 1: odd).
+__device__ __forceinline__ void gauss_pair(uint32_t w0, uint32_t w1, float &eps0, float &eps1)
+{
+    const float L = ln_u1((w0 >> 8) + 1u);
+    const float r = __builtin_sqrtf(-2.0f * L);   // correctly rounded (hipcc default for fp32 sqrt)
+    const float f = (float)((w1 >> 6) & 0xFFFFFFu) * 0x1p-24f;
+    const float z = f * f;
+    float sp = 0x1.3e17cap-13f;
+    sp = __builtin_fmaf(sp, z, -0x1.32535ap-8f);
+    sp = __builtin_fmaf(sp, z, 0x1.4668f2p-4f);
+    sp = __builtin_fmaf(sp, z, -0x1.4abbc4p-1f);
+    sp = __builtin_fmaf(sp, z, 0x1.921fb6p+0f);
+    float c = 0x1.c1f064p-11f;
+    c = __builtin_fmaf(c, z, -0x1.54f61ap-6f);
+    c = __builtin_fmaf(c, z, 0x1.03bd06p-2f);
+    c = __builtin_fmaf(c, z, -0x1.3bd3a6p+0f);
+    c = __builtin_fmaf(c, z, 0x1.fffffep-1f);
+    const float s = f * sp;
+    // quadrant q = w1 >> 30: (c,s), (-s,c), (-c,-s), (s,-c)
+    const bool swap = (w1 & 0x40000000u) != 0u;
+    const float a = swap ? s : c;
+    const float b = swap ? c : s;
+    const uint32_t sign_a = (w1 ^ (w1 << 1)) & 0x80000000u;   // q = 1 or 2
+    const uint32_t sign_b = w1 & 0x80000000u;                 // q = 2 or 3
+    const float ca = __uint_as_float(__float_as_uint(a) ^ sign_a);
+    const float sb = __uint_as_float(__float_as_uint(b) ^ sign_b);
+    eps0 = r * ca;
+    eps1 = r * sb;
+}
+
+// N5 + N6. One lane's integer perturbation from its Gaussian and its rounding word.
+__device__ __forceinline__ int32_t delta_of(float eps, uint32_t wround, float sigma)
+{
+    const float ub = (float)(wround >> 8) * 0x1p-24f;
+    const float t = sigma * eps;
+    const float fl = __builtin_floorf(t);
+    const float fr = t - fl;
+    int32_t d = (int32_t)fl + ((ub < fr) ? 1 : 0);
+    d = d < -8 ? -8 : d;
+    d = d > 7 ? 7 : d;
+    return d;
+}
+
+// The two perturbations of pair `pair` (32-bit pair index, high counter word 0) of a tensor.
+__device__ __forceinline__ void delta_pair(uint32_t k0, uint32_t k1, uint32_t tensor_id,
+                                           uint32_t pair, float sigma, int32_t &d0, int32_t &d1)
+{
+    const Words w = philox4x32_10(pair, 0u, tensor_id, 0u, k0, k1);
+    float e0, e1;
+    gauss_pair(w.w0, w.w1, e0, e1);
+    d0 = delta_of(e0, w.w2, sigma);
+    d1 = delta_of(e1, w.w3, sigma);
+}
+
+// N7 / Alg. 2 gate: v if qmin <= v <= qmax else keep.
+__device__ __forceinline__ int32_t gate(int32_t base, int32_t delta, int32_t qmin, uint32_t qspan)
+{
+    const uint32_t v = (uint32_t)base + (uint32_t)delta;   // wraps instead of overflowing
+    return (v - (uint32_t)qmin <= qspan) ? (int32_t)v : base;
+}
+
+}  // namespace qes

@@ -1,0 +1,131 @@
+// Noise probes (bit-for-bit test access to the generator of docs/NOISE_SPEC.md) and the two
+// ceiling microbenchmarks the benchmark reports next to the kernels: noise draws per second with
+// no memory traffic, and a plain streaming copy.
+#include "qes_internal.hpp"
+#include "qes_noise.hpp"
+
+namespace qes {
+
+namespace {
+
+constexpr int kBlock = 256;
+
+__global__ __launch_bounds__(kBlock) void noise_words_kernel(uint32_t k0, uint32_t k1, uint32_t tensor_id,
+                                                              uint64_t pair_begin, uint64_t n_pairs,
+                                                              uint4 *__restrict__ out)
+{
+    const uint64_t j = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (j >= n_pairs) return;
+    const uint64_t pair = pair_begin + j;
+    const Words w = philox4x32_10((uint32_t)pair, (uint32_t)(pair >> 32), tensor_id, 0u, k0, k1);
+    out[j] = make_uint4(w.w0, w.w1, w.w2, w.w3);
+}
+
+// MODE 0: Gaussian (float), MODE 1: delta (int8). One thread per pair touching the window.
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void noise_elems_kernel(uint32_t k0, uint32_t k1, uint32_t tensor_id,
+                                                             uint64_t elem_begin, uint64_t n_elems,
+                                                             float sigma, void *__restrict__ out)
+{
+    const uint64_t first_pair = elem_begin >> 1;
+    const uint64_t j = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t pair = first_pair + j;
+    const uint64_t e0 = pair << 1;
+    if (e0 >= elem_begin + n_elems) return;
+    const Words w = philox4x32_10((uint32_t)pair, (uint32_t)(pair >> 32), tensor_id, 0u, k0, k1);
+    float g0, g1;
+    gauss_pair(w.w0, w.w1, g0, g1);
+    const float g[2] = {g0, g1};
+    const uint32_t wr[2] = {w.w2, w.w3};
+#pragma unroll
+    for (int l = 0; l < 2; ++l) {
+        const uint64_t e = e0 + l;
+        if (e < elem_begin || e >= elem_begin + n_elems) continue;
+        if (MODE == 0) ((float *)out)[e - elem_begin] = g[l];
+        else ((int8_t *)out)[e - elem_begin] = (int8_t)delta_of(g[l], wr[l], sigma);
+    }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void bench_noise_kernel(uint64_t n_threads, int iters, float sigma,
+                                                             uint32_t *__restrict__ sink)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (t >= n_threads) return;
+    uint32_t acc = 0;
+    const uint32_t pair = (uint32_t)t;
+    // the key changes per iteration and is wave-uniform, as in the real kernels (one member per step)
+    for (int it = 0; it < iters; ++it) {
+        const uint32_t k0 = 0x1234567u + (uint32_t)it * 0x9E3779B1u;
+        const uint32_t k1 = 0x89ABCDEu ^ (uint32_t)it;
+        if (MODE == 0) {
+            const Words w = philox4x32_10(pair, 0u, 7u, 0u, k0, k1);
+            acc ^= w.w0 ^ w.w1 ^ w.w2 ^ w.w3;
+        } else {
+            int32_t d0, d1;
+            delta_pair(k0, k1, 7u, pair, sigma, d0, d1);
+            acc += (uint32_t)(d0 * 16 + d1);
+        }
+    }
+    sink[t] = acc;
+}
+
+__global__ __launch_bounds__(kBlock) void copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                      size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += stride)
+        dst[i] = src[i];
+}
+
+inline unsigned blocks_for(uint64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
+
+}  // namespace
+
+hipError_t launch_noise_words(uint64_t seed, uint32_t tensor_id, uint64_t pair_begin, uint64_t n_pairs,
+                              uint32_t *out4, hipStream_t s)
+{
+    noise_words_kernel<<<blocks_for(n_pairs), kBlock, 0, s>>>((uint32_t)seed, (uint32_t)(seed >> 32), tensor_id,
+                                                            pair_begin, n_pairs, (uint4 *)out4);
+    return hipGetLastError();
+}
+
+hipError_t launch_noise_gauss(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint64_t n,
+                              float *out, hipStream_t s)
+{
+    const uint64_t pairs = ((elem_begin + n + 1) >> 1) - (elem_begin >> 1);
+    noise_elems_kernel<0><<<blocks_for(pairs), kBlock, 0, s>>>((uint32_t)seed, (uint32_t)(seed >> 32), tensor_id,
+                                                             elem_begin, n, 0.0f, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_noise_delta(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint64_t n,
+                              float sigma, int8_t *out, hipStream_t s)
+{
+    const uint64_t pairs = ((elem_begin + n + 1) >> 1) - (elem_begin >> 1);
+    noise_elems_kernel<1><<<blocks_for(pairs), kBlock, 0, s>>>((uint32_t)seed, (uint32_t)(seed >> 32), tensor_id,
+                                                             elem_begin, n, sigma, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_bench_noise(int mode, uint64_t n_threads, int iters, float sigma, uint32_t *sink,
+                              hipStream_t s)
+{
+    if (mode == 0)
+        bench_noise_kernel<0><<<blocks_for(n_threads), kBlock, 0, s>>>(n_threads, iters, sigma, sink);
+    else
+        bench_noise_kernel<1><<<blocks_for(n_threads), kBlock, 0, s>>>(n_threads, iters, sigma, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_bench_copy(const void *src, void *dst, size_t n_bytes, hipStream_t s)
+{
+    const size_t n16 = n_bytes / 16;
+    size_t blocks = (n16 + kBlock - 1) / kBlock;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks == 0) return hipSuccess;
+    copy_kernel<<<(unsigned)blocks, kBlock, 0, s>>>((const uint4 *)src, (uint4 *)dst, n16);
+    return hipGetLastError();
+}
+
+}  // namespace qes

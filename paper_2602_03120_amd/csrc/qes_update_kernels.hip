@@ -1,0 +1,199 @@
+// Seeded error-feedback update with stateless seed replay (paper §3.3 Alg. 2; §3.2 Eq. 5-8).
+//
+// One thread owns PPT consecutive pairs of K-adjacent elements (PPT bytes of packed INT4, or
+// 2*PPT bytes of INT8) and walks the generations oldest -> newest, regenerating every member's
+// perturbation from its seed. Nothing but the packed weights is read from or written to HBM:
+// (seed, fitness) records are wave-uniform and come through the scalar cache. The kernels are
+// bound by the vector ALU work of the noise generator, so the layout goal is only that memory
+// never appears on the critical path: one coalesced load and (if anything changed) one coalesced
+// store per thread.
+//
+// Arithmetic order is part of the definition (bit-exact integer results):
+//   g = fma(F_i, δ_i, g) for i = 0..N-1;  u = fma(c, g, γ*e);  Δ = rne(u);  e = u - Δ_gated.
+#include "qes_internal.hpp"
+#include "qes_noise.hpp"
+
+namespace qes {
+
+namespace {
+
+constexpr int kBlock = 256;
+
+template <int BITS>
+struct Pack;
+
+template <>
+struct Pack<4> {
+    // one byte = one pair
+    __device__ static __forceinline__ void unpack(uint32_t byte, int32_t &a, int32_t &b)
+    {
+        a = ((int32_t)(byte << 28)) >> 28;
+        b = ((int32_t)(byte << 24)) >> 28;
+    }
+    __device__ static __forceinline__ uint32_t pack(int32_t a, int32_t b)
+    {
+        return ((uint32_t)a & 0xFu) | (((uint32_t)b & 0xFu) << 4);
+    }
+    static constexpr int kBytesPerPair = 1;
+};
+
+template <>
+struct Pack<8> {
+    // two bytes = one pair
+    __device__ static __forceinline__ void unpack(uint32_t half, int32_t &a, int32_t &b)
+    {
+        a = ((int32_t)(half << 24)) >> 24;
+        b = ((int32_t)(half << 16)) >> 24;
+    }
+    __device__ static __forceinline__ uint32_t pack(int32_t a, int32_t b)
+    {
+        return ((uint32_t)a & 0xFFu) | (((uint32_t)b & 0xFFu) << 8);
+    }
+    static constexpr int kBytesPerPair = 2;
+};
+
+// raw bytes of PPT pairs, as 32-bit words where possible
+template <int BYTES>
+struct Raw {
+    static_assert(BYTES == 1 || BYTES == 2 || BYTES % 4 == 0, "unsupported width");
+    static constexpr int kWords = BYTES >= 4 ? BYTES / 4 : 1;
+    uint32_t w[kWords];
+
+    __device__ __forceinline__ void load(const void *base, size_t byte_off)
+    {
+        const char *p = (const char *)base + byte_off;
+        if (BYTES == 1) w[0] = *(const uint8_t *)p;
+        else if (BYTES == 2) w[0] = *(const uint16_t *)p;
+        else {
+#pragma unroll
+            for (int i = 0; i < kWords; ++i) w[i] = ((const uint32_t *)p)[i];
+        }
+    }
+    __device__ __forceinline__ void store(void *base, size_t byte_off) const
+    {
+        char *p = (char *)base + byte_off;
+        if (BYTES == 1) *(uint8_t *)p = (uint8_t)w[0];
+        else if (BYTES == 2) *(uint16_t *)p = (uint16_t)w[0];
+        else {
+#pragma unroll
+            for (int i = 0; i < kWords; ++i) ((uint32_t *)p)[i] = w[i];
+        }
+    }
+    // the bits of pair j
+    __device__ __forceinline__ uint32_t pair_bits(int j, int bytes_per_pair) const
+    {
+        const int bit = j * bytes_per_pair * 8;
+        return (w[bit >> 5] >> (bit & 31)) & (bytes_per_pair == 1 ? 0xFFu : 0xFFFFu);
+    }
+    __device__ __forceinline__ void set_pair_bits(int j, int bytes_per_pair, uint32_t v)
+    {
+        const int bit = j * bytes_per_pair * 8;
+        const uint32_t mask = (bytes_per_pair == 1 ? 0xFFu : 0xFFFFu) << (bit & 31);
+        w[bit >> 5] = (w[bit >> 5] & ~mask) | (v << (bit & 31));
+    }
+};
+
+template <int BITS, int PPT, bool RESIDUAL>
+__global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
+{
+    using P = Pack<BITS>;
+    constexpr int kBytes = PPT * P::kBytesPerPair;
+    const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t pair0 = t * PPT;
+    if (pair0 >= a.n_pairs) return;   // n_pairs is a multiple of PPT (checked on the host)
+
+    Raw<kBytes> raw;
+    raw.load(a.qweight, (size_t)t * kBytes);
+    int32_t wq[2 * PPT];
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) P::unpack(raw.pair_bits(j, P::kBytesPerPair), wq[2 * j], wq[2 * j + 1]);
+
+    float res[2 * PPT];
+#pragma unroll
+    for (int j = 0; j < 2 * PPT; ++j) res[j] = 0.0f;
+
+    uint32_t changed = 0, gated = 0;
+    const Entry *__restrict__ ent = a.entries;
+    for (int32_t tau = 0; tau < a.steps; ++tau) {
+        float g[2 * PPT];
+#pragma unroll
+        for (int j = 0; j < 2 * PPT; ++j) g[j] = 0.0f;
+        for (int32_t i = 0; i < a.N; ++i) {
+            const Entry en = ent[tau * a.N + i];          // wave-uniform: scalar load
+            const float fit = __uint_as_float(en.fit_bits);
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) {
+                int32_t d0, d1;
+                delta_pair(en.seed_lo, en.seed_hi, a.tensor_id, pair0 + j, a.sigma, d0, d1);
+                g[2 * j] = __builtin_fmaf(fit, (float)d0, g[2 * j]);
+                g[2 * j + 1] = __builtin_fmaf(fit, (float)d1, g[2 * j + 1]);
+            }
+        }
+        const bool last = !RESIDUAL && (tau == a.steps - 1);
+#pragma unroll
+        for (int j = 0; j < 2 * PPT; ++j) {
+            const float u = __builtin_fmaf(a.c, g[j], a.gamma * res[j]);
+            const int32_t d = (int32_t)__builtin_rintf(u);
+            const int32_t nv = gate(wq[j], d, a.qmin, a.qspan);
+            const int32_t df = nv - wq[j];
+            res[j] = u - (float)df;
+            if (last) {
+                changed += (df != 0);
+                gated += (df == 0 && d != 0);
+                wq[j] = nv;
+            }
+        }
+    }
+
+    if (RESIDUAL) {
+        float *out = a.residual + (size_t)pair0 * 2;
+#pragma unroll
+        for (int j = 0; j < 2 * PPT; ++j) out[j] = res[j];
+    } else {
+        if (changed) {
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) raw.set_pair_bits(j, P::kBytesPerPair, P::pack(wq[2 * j], wq[2 * j + 1]));
+            raw.store(a.qweight, (size_t)t * kBytes);
+        }
+        if (a.stats) {
+            // wavefront reduction, then one atomic per wave and counter
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                changed += __shfl_xor(changed, off);
+                gated += __shfl_xor(gated, off);
+            }
+            if ((threadIdx.x & 63) == 0) {
+                if (changed) atomicAdd(&a.stats[0], (unsigned long long)changed);
+                if (gated) atomicAdd(&a.stats[1], (unsigned long long)gated);
+            }
+        }
+    }
+}
+
+template <int BITS, bool RESIDUAL>
+hipError_t launch_ppt(const UpdateArgs &a, hipStream_t s)
+{
+    // Enough threads to fill 256 CUs x 4 SIMDs several waves deep, else fewer pairs per thread.
+    const uint64_t want_threads = 256ull * 4 * 64 * 4;
+    int ppt = 4;
+    while (ppt > 1 && ((a.n_pairs % ppt) != 0 || a.n_pairs / ppt < want_threads)) ppt >>= 1;
+    const uint64_t threads = a.n_pairs / ppt;
+    const unsigned blocks = (unsigned)((threads + kBlock - 1) / kBlock);
+    switch (ppt) {
+    case 4: update_kernel<BITS, 4, RESIDUAL><<<blocks, kBlock, 0, s>>>(a); break;
+    case 2: update_kernel<BITS, 2, RESIDUAL><<<blocks, kBlock, 0, s>>>(a); break;
+    default: update_kernel<BITS, 1, RESIDUAL><<<blocks, kBlock, 0, s>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_update(const UpdateArgs &a, int bits, bool residual, hipStream_t s)
+{
+    if (a.n_pairs == 0) return hipSuccess;
+    if (bits == 4) return residual ? launch_ppt<4, true>(a, s) : launch_ppt<4, false>(a, s);
+    return residual ? launch_ppt<8, true>(a, s) : launch_ppt<8, false>(a, s);
+}
+
+}  // namespace qes

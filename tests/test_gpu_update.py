@@ -1,0 +1,141 @@
+"""GPU parity: qes_update / qes_replay_residual against the CPU oracle (paper Alg. 2, Eq. 5-8).
+
+Integer weights and the diagnostics counters must match bit for bit. The fp32 residual is produced
+by the same fp32 operations in the same order on both sides, so it is compared for exact equality
+as well (the stated tolerance of 1e-5 relative is the fallback bar and is asserted too).
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env(oracle):
+    import torch
+    import paper_2602_03120_amd as qes
+    import gpu_util
+    assert torch.cuda.is_available()
+    return dict(torch=torch, qes=qes, u=gpu_util, oracle=oracle)
+
+
+def _history(rng, oracle, K, N):
+    seeds = rng.integers(0, 2 ** 63, size=(K + 1, N), dtype=np.uint64)
+    if N == 1:      # a z-score of one member is 0: use raw fitnesses so that the case is not vacuous
+        fit = rng.standard_normal((K + 1, 1)).astype(np.float32)
+    else:
+        fit = np.stack([oracle.normalize_fitness(rng.standard_normal(N).astype(np.float32)) for _ in range(K + 1)])
+    return seeds, fit
+
+
+def _run_update(env, ot, seeds, fit, K, sigma, alpha, gamma, rows=None):
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    dt = u.device_tensor(ot)
+    stats = torch.zeros(2, dtype=torch.int64, device=u.DEV)
+    qes.update(dt, seeds[K], fit[K], seeds[:K], fit[:K], sigma, alpha, gamma, stats=stats)
+    got = dt.qweight.cpu().numpy()
+    ref_t = ot.copy()
+    ref_stats = oracle.update(ref_t, seeds[K], fit[K], seeds[:K], fit[:K], sigma, alpha, gamma, rows=rows)
+    return got, ref_t, stats.cpu().numpy().view(np.uint64), ref_stats
+
+
+# shapes chosen to hit 1, 2 and 4 pairs per thread, several blocks and ragged tails
+@pytest.mark.parametrize("bits,out_f,in_f,K,N", [
+    (4, 256, 256, 4, 8),        # config 1 layer
+    (4, 7, 34, 3, 5),           # tiny, odd pair count
+    (4, 1024, 2050, 2, 3),      # n_pairs % 4 != 0 -> fewer pairs per thread
+    (4, 2048, 1024, 1, 4),      # 1M pairs: 4 pairs per thread
+    (4, 1024, 1024, 2, 4),      # 512K pairs: 2 pairs per thread
+    (8, 129, 66, 3, 6),
+    (8, 2048, 1024, 1, 3),
+    (8, 1024, 1024, 2, 2),
+    (4, 64, 128, 0, 8),         # no history: stateless deterministic rounding (Eq. 9)
+    (8, 64, 128, 5, 1),         # population of one
+])
+def test_update_bit_exact(env, bits, out_f, in_f, K, N):
+    oracle = env["oracle"]
+    qw, _, qmin, qmax = wl.random_tensor(100 + out_f + in_f, out_f, in_f, bits, 0)
+    ot = oracle.Tensor(qw, None, out_f, in_f, bits, 0, qmin, qmax, 42)
+    rng = np.random.default_rng(out_f * 7 + in_f)
+    seeds, fit = _history(rng, oracle, K, N)
+    got, ref_t, stats, ref_stats = _run_update(env, ot, seeds, fit, K, 1.0, 1.5, 0.9)
+    assert (got.view(np.uint8) == ref_t.qweight.view(np.uint8)).all()
+    assert (stats == ref_stats).all()
+    assert ref_stats[0] > 0                       # the case is not vacuous: weights moved
+    if out_f * in_f > 10000:
+        assert ref_stats[1] > 0                   # and the gate fired (uniform weights sit on edges)
+
+
+@pytest.mark.parametrize("sigma,alpha,gamma", [(1.0, 0.5, 0.9), (0.01, 5e-4, 0.9), (2.5, 3.0, 1.0), (0.7, 0.3, 0.0)])
+def test_update_hyperparameters(env, sigma, alpha, gamma):
+    oracle = env["oracle"]
+    qw, _, qmin, qmax = wl.random_tensor(5, 96, 160, 4, 0)
+    ot = oracle.Tensor(qw, None, 96, 160, 4, 0, qmin, qmax, 9)
+    seeds, fit = _history(np.random.default_rng(3), oracle, 6, 10)
+    got, ref_t, stats, ref_stats = _run_update(env, ot, seeds, fit, 6, sigma, alpha, gamma)
+    assert (got == ref_t.qweight).all() and (stats == ref_stats).all()
+
+
+@pytest.mark.parametrize("bits,out_f,in_f,K,N", [(4, 256, 256, 4, 8), (4, 33, 70, 7, 5), (8, 1024, 1024, 2, 3),
+                                                 (4, 2048, 1024, 1, 2), (8, 16, 32, 0, 4)])
+def test_replay_residual(env, bits, out_f, in_f, K, N):
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    qw, _, qmin, qmax = wl.random_tensor(200 + out_f, out_f, in_f, bits, 0)
+    ot = oracle.Tensor(qw, None, out_f, in_f, bits, 0, qmin, qmax, 77)
+    seeds, fit = _history(np.random.default_rng(out_f), oracle, K, N)
+    dt = u.device_tensor(ot)
+    res = torch.full((out_f, in_f), 123.0, dtype=torch.float32, device=u.DEV)
+    qes.replay_residual(dt, seeds[:K], fit[:K], N, 1.0, 1.5, 0.9, res)
+    got = res.cpu().numpy()
+    ref = oracle.replay_residual(ot, seeds[:K], fit[:K], N, 1.0, 1.5, 0.9)
+    assert np.abs(got - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max())     # stated tolerance
+    assert (got.view(np.uint32) == ref.view(np.uint32)).all()                # and in fact identical
+    assert (dt.qweight.cpu().numpy() == ot.qweight).all()                    # weights untouched
+    if K > 0:
+        assert np.abs(ref).max() > 0
+
+
+def test_zero_fitness_variance_leaves_weights(env):
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    qw, _, qmin, qmax = wl.random_tensor(1, 128, 128, 4, 0)
+    ot = oracle.Tensor(qw, None, 128, 128, 4, 0, qmin, qmax, 1)
+    dt = u.device_tensor(ot)
+    N, K = 8, 3
+    seeds = np.arange((K + 1) * N, dtype=np.uint64).reshape(K + 1, N)
+    fit = np.tile(qes.normalize_fitness(np.full(N, 2.5, dtype=np.float32)), (K + 1, 1))
+    assert (fit == 0).all()
+    stats = torch.zeros(2, dtype=torch.int64, device=u.DEV)
+    qes.update(dt, seeds[K], fit[K], seeds[:K], fit[:K], 1.0, 0.5, 0.9, stats=stats)
+    assert (dt.qweight.cpu().numpy() == ot.qweight).all()
+    assert (stats.cpu().numpy() == 0).all()
+
+
+def test_normalize_fitness_matches_oracle(env):
+    qes, oracle = env["qes"], env["oracle"]
+    rng = np.random.default_rng(8)
+    for n in (1, 2, 30, 1024):
+        r = (rng.standard_normal(n) * 4 - 1).astype(np.float32)
+        assert (qes.normalize_fitness(r) == oracle.normalize_fitness(r)).all()
+
+
+def test_update_argument_errors(env):
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    qw, _, qmin, qmax = wl.random_tensor(1, 16, 32, 4, 0)
+    dt = u.device_tensor(oracle.Tensor(qw, None, 16, 32, 4, 0, qmin, qmax, 1))
+    seeds = np.arange(4, dtype=np.uint64)
+    fit = np.zeros(4, dtype=np.float32)
+    before = dt.qweight.clone()
+    for kwargs in (dict(sigma=0.0), dict(sigma=-1.0), dict(gamma=1.5), dict(alpha=float("inf"))):
+        args = dict(sigma=1.0, alpha=0.5, gamma=0.9)
+        args.update(kwargs)
+        with pytest.raises(qes.QesError) as ei:
+            qes.update(dt, seeds, fit, None, None, args["sigma"], args["alpha"], args["gamma"])
+        assert ei.value.status == -1
+    bad = fit.copy()
+    bad[2] = np.nan
+    with pytest.raises(qes.QesError):
+        qes.update(dt, seeds, bad, None, None, 1.0, 0.5, 0.9)
+    torch.cuda.synchronize()
+    assert (dt.qweight == before).all()

@@ -1,0 +1,42 @@
+"""The C-ABI library loads and exports every symbol include/qes.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "qes.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qes_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    import paper_2602_03120_amd.binding as b
+    lib = ctypes.CDLL(b.library_path())
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(b.EXPORTS) == names
+
+
+def test_host_only_entry_points():
+    import paper_2602_03120_amd as qes
+    assert qes.abi_version() == 1
+    assert qes.status_string(0) == "ok" and "invalid" in qes.status_string(-1)
+    f = qes.normalize_fitness(np.array([1, 2, 3, 4, 5], dtype=np.float32))
+    assert abs(f.mean()) < 1e-7 and abs(f.std() - 1) < 1e-6
+    assert (qes.normalize_fitness(np.full(7, 2.0, dtype=np.float32)) == 0).all()
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2602_03120_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".hpp", ".h")):
+                src = open(os.path.join(dirpath, fn)).read()
+                assert "import oracle" not in src and "from oracle" not in src and "qes_oracle" not in src, fn
