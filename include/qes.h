@@ -94,6 +94,15 @@ int qes_noise_gauss(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint
 int qes_noise_delta(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint64_t n_elems,
                     float sigma, int8_t *out, void *stream);
 
+/*
+ * N3-N6 of docs/NOISE_SPEC.md applied to caller-supplied Philox words instead of generated ones:
+ * for each of n word quadruples, the two Gaussians (eps2, DEVICE float32 [n][2], may be NULL) and
+ * the two perturbations (delta2, DEVICE int8 [n][2], may be NULL). Lets a test sweep the radius
+ * and angle inputs exhaustively. words4: DEVICE uint32 [n][4], 16-byte aligned.
+ */
+int qes_noise_from_words(const uint32_t *words4, uint64_t n, float sigma, float *eps2, int8_t *delta2,
+                         void *stream);
+
 /* ---- population evaluation (Alg. 1, steps "reconstruct δ_i", "W' = Gate(W_t+δ_i)", inference) ---- */
 
 /*

@@ -48,6 +48,8 @@ def lib():
         L.oracle_noise_gauss.restype = None
         L.oracle_noise_delta.argtypes = [u64, u32, u64, u64, f32, vp]
         L.oracle_noise_delta.restype = None
+        L.oracle_noise_from_words.argtypes = [vp, u64, f32, vp, vp]
+        L.oracle_noise_from_words.restype = None
         L.oracle_delta_from_gauss.argtypes = [f32, u32, f32]
         L.oracle_delta_from_gauss.restype = i32
         L.oracle_perturbed_qgemm.argtypes = [tp, vp, vp, i32, f32, vp, i32, vp, i32, vp, i32]
@@ -152,6 +154,16 @@ def noise_delta(seed, tensor_id, elem_begin, n_elems, sigma):
     out = np.empty(n_elems, dtype=np.int8)
     lib().oracle_noise_delta(seed, tensor_id, elem_begin, n_elems, sigma, _ptr(out))
     return out
+
+
+def noise_from_words(words, sigma):
+    """words: uint32 [n,4] -> (eps float32 [n,2], delta int8 [n,2])."""
+    words = _c(words, np.uint32).reshape(-1, 4)
+    n = words.shape[0]
+    eps = np.empty((n, 2), dtype=np.float32)
+    delta = np.empty((n, 2), dtype=np.int8)
+    lib().oracle_noise_from_words(_ptr(words), n, sigma, _ptr(eps), _ptr(delta))
+    return eps, delta
 
 
 def delta_from_gauss(eps, wround, sigma):

@@ -218,6 +218,20 @@ void oracle_noise_delta(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, 
         out[i] = (int8_t)delta_of_element(seed, tensor_id, elem_begin + i, sigma);
 }
 
+/* N3-N6 on caller-supplied words: Gaussians and perturbations of n word quadruples */
+void oracle_noise_from_words(const uint32_t *words4, uint64_t n, float sigma, float *eps2, int8_t *delta2)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        float eps[2];
+        words_to_gauss(words4 + 4 * i, eps);
+        if (eps2) { eps2[2 * i] = eps[0]; eps2[2 * i + 1] = eps[1]; }
+        if (delta2) {
+            delta2[2 * i] = (int8_t)gauss_to_delta(eps[0], words4[4 * i + 2], sigma);
+            delta2[2 * i + 1] = (int8_t)gauss_to_delta(eps[1], words4[4 * i + 3], sigma);
+        }
+    }
+}
+
 /* δ for a caller-supplied Gaussian and rounding word: lets a test enumerate the rounding uniform */
 int32_t oracle_delta_from_gauss(float eps, uint32_t wround, float sigma)
 {

@@ -5,9 +5,9 @@ used for device memory and streams, nothing else. There is no CPU fallback: impo
 without a built library raises.
 """
 from .binding import (QesError, Tensor, abi_version, bench_copy, bench_noise, gemm_workspace_bytes,
-                      library_path, noise_delta, noise_gauss, noise_words, normalize_fitness,
+                      library_path, noise_delta, noise_from_words, noise_gauss, noise_words, normalize_fitness,
                       perturbed_qgemm, replay_residual, status_string, update)
 
 __all__ = ["QesError", "Tensor", "abi_version", "bench_copy", "bench_noise", "gemm_workspace_bytes",
-           "library_path", "noise_delta", "noise_gauss", "noise_words", "normalize_fitness",
+           "library_path", "noise_delta", "noise_from_words", "noise_gauss", "noise_words", "normalize_fitness",
            "perturbed_qgemm", "replay_residual", "status_string", "update"]

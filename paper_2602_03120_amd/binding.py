@@ -54,6 +54,7 @@ def _load():
         "qes_noise_words": ([u64, u32, u64, u64, vp, vp], i32),
         "qes_noise_gauss": ([u64, u32, u64, u64, vp, vp], i32),
         "qes_noise_delta": ([u64, u32, u64, u64, f32, vp, vp], i32),
+        "qes_noise_from_words": ([vp, u64, f32, vp, vp, vp], i32),
         "qes_perturbed_qgemm": ([tp, vp, vp, i32, f32, vp, i32, vp, i32, vp, sz, vp], i32),
         "qes_gemm_workspace_bytes": ([tp, i32, i32, i32], sz),
         "qes_update": ([tp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
@@ -73,7 +74,7 @@ def _load():
     return L
 
 
-EXPORTS = ["qes_noise_words", "qes_noise_gauss", "qes_noise_delta", "qes_perturbed_qgemm",
+EXPORTS = ["qes_noise_words", "qes_noise_gauss", "qes_noise_delta", "qes_noise_from_words", "qes_perturbed_qgemm",
            "qes_gemm_workspace_bytes", "qes_update", "qes_replay_residual", "qes_normalize_fitness",
            "qes_bench_noise", "qes_bench_copy", "qes_status_string", "qes_last_hip_error",
            "qes_abi_version"]
@@ -152,6 +153,12 @@ def noise_gauss(seed, tensor_id, elem_begin, n_elems, out, stream=None):
 def noise_delta(seed, tensor_id, elem_begin, n_elems, sigma, out, stream=None):
     _check(_load().qes_noise_delta(seed, tensor_id, elem_begin, n_elems, sigma, _dev_ptr(out, "out"),
                                    _stream(stream)), "qes_noise_delta")
+
+
+def noise_from_words(words, n, sigma, eps2=None, delta2=None, stream=None):
+    """words: device int32/uint32 [n,4]; eps2: device float32 [n,2] or None; delta2: device int8 [n,2] or None."""
+    _check(_load().qes_noise_from_words(_dev_ptr(words, "words"), n, sigma, _dev_ptr(eps2, "eps2"),
+                                        _dev_ptr(delta2, "delta2"), _stream(stream)), "qes_noise_from_words")
 
 
 def gemm_workspace_bytes(w, N, T, act_mode):

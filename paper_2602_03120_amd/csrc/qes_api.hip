@@ -226,6 +226,16 @@ int qes_noise_delta(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint
     return QES_OK;
 }
 
+int qes_noise_from_words(const uint32_t *words4, uint64_t n, float sigma, float *eps2, int8_t *delta2, void *stream)
+{
+    if (n == 0) return QES_OK;
+    if (!words4 || ((uintptr_t)words4 & 15u) != 0 || n > (1ull << 31)) return QES_ERR_INVALID_ARG;
+    if ((eps2 && ((uintptr_t)eps2 & 7u) != 0) || (delta2 && ((uintptr_t)delta2 & 1u) != 0)) return QES_ERR_INVALID_ARG;
+    if (!(sigma >= 0.0f) || !std::isfinite(sigma)) return QES_ERR_INVALID_ARG;
+    QES_HIP(qes::launch_noise_from_words(words4, n, sigma, eps2, delta2, (hipStream_t)stream));
+    return QES_OK;
+}
+
 size_t qes_gemm_workspace_bytes(const qes_tensor *w, int32_t N, int32_t T, int32_t act_mode)
 {
     if (!w || act_mode != 1 || N <= 0 || T <= 0) return 0;

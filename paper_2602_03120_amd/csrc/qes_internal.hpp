@@ -48,6 +48,8 @@ hipError_t launch_noise_gauss(uint64_t seed, uint32_t tensor_id, uint64_t elem_b
                               float *out, hipStream_t s);
 hipError_t launch_noise_delta(uint64_t seed, uint32_t tensor_id, uint64_t elem_begin, uint64_t n,
                               float sigma, int8_t *out, hipStream_t s);
+hipError_t launch_noise_from_words(const uint32_t *words4, uint64_t n, float sigma, float *eps2, int8_t *delta2,
+                                   hipStream_t s);
 hipError_t launch_bench_noise(int mode, uint64_t n_threads, int iters, float sigma, uint32_t *sink,
                               hipStream_t s);
 hipError_t launch_bench_copy(const void *src, void *dst, size_t n_bytes, hipStream_t s);

@@ -40,6 +40,74 @@ __device__ __forceinline__ Words philox4x32_10(uint32_t c0, uint32_t c1, uint32_
     return Words{c0, c1, c2, c3};
 }
 
+// Three-input xor in one instruction (gfx950 v_bitop3_b32, truth table 0x96).
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
+// N1 + N2 for the tensor kernels: counter (pair, 0, tensor_id, 0) with a wave-uniform key and
+// tensor id. Same function as philox4x32_10(pair, 0, tensor_id, 0, k0, k1); written round by round
+// so that everything that does not depend on the lane is computed on the scalar unit (the second
+// product of round 1, the first product of round 2, the pre-xored round keys) and every
+// three-input xor of lane data is a single instruction.
+__device__ __forceinline__ Words philox_tensor(uint32_t pair, uint32_t tensor_id, uint32_t k0, uint32_t k1)
+{
+    // round 1
+    uint64_t p0 = (uint64_t)kPhiloxM0 * (uint64_t)pair;
+    const uint64_t u1 = (uint64_t)kPhiloxM1 * (uint64_t)tensor_id;           // uniform
+    const uint32_t c0_1 = (uint32_t)(u1 >> 32) ^ k0;                          // uniform
+    const uint32_t c1_1 = (uint32_t)u1;                                       // uniform
+    uint32_t c2 = (uint32_t)(p0 >> 32) ^ k1;
+    uint32_t c3 = (uint32_t)p0;
+    k0 += kPhiloxW0;
+    k1 += kPhiloxW1;
+    // round 2
+    const uint64_t u0 = (uint64_t)kPhiloxM0 * (uint64_t)c0_1;                 // uniform
+    uint64_t p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
+    uint32_t c0 = (uint32_t)(p1 >> 32) ^ (c1_1 ^ k0);
+    uint32_t c1 = (uint32_t)p1;
+    c2 = c3 ^ ((uint32_t)(u0 >> 32) ^ k1);
+    const uint32_t c3_2 = (uint32_t)u0;                                       // uniform
+    k0 += kPhiloxW0;
+    k1 += kPhiloxW1;
+    // round 3
+    p0 = (uint64_t)kPhiloxM0 * (uint64_t)c0;
+    p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
+    c0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+    c2 = (uint32_t)(p0 >> 32) ^ (c3_2 ^ k1);
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    // rounds 4..10
+#pragma unroll
+    for (int r = 3; r < 10; ++r) {
+        k0 += kPhiloxW0;
+        k1 += kPhiloxW1;
+        p0 = (uint64_t)kPhiloxM0 * (uint64_t)c0;
+        p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
+        c0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+        c2 = xor3((uint32_t)(p0 >> 32), c3, k1);
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+    }
+    return Words{c0, c1, c2, c3};
+}
+
+// Correctly rounded sqrt for x in {-0} U [2^-24, 64): the hardware approximation (within one
+// ulp) followed by the usual one-ulp correction against the exact residual. No range scaling is
+// needed because x = -2 ln(u1) is never subnormal.
+__device__ __forceinline__ float sqrt_rn_bounded(float x)
+{
+    const float s = __builtin_amdgcn_sqrtf(x);
+    const float s_dn = __uint_as_float(__float_as_uint(s) - 1u);
+    const float s_up = __uint_as_float(__float_as_uint(s) + 1u);
+    const float r_dn = __builtin_fmaf(-s_dn, s, x);
+    const float r_up = __builtin_fmaf(-s_up, s, x);
+    float r = (r_dn <= 0.0f) ? s_dn : s;
+    r = (r_up > 0.0f) ? s_up : r;
+    return r;
+}
+
 // N4. ln(m * 2^-24) for integer m in [1, 2^24]; result <= 0.
 __device__ __forceinline__ float ln_u1(uint32_t m)
 {
@@ -62,7 +130,7 @@ __device__ __forceinline__ float ln_u1(uint32_t m)
 __device__ __forceinline__ void gauss_pair(uint32_t w0, uint32_t w1, float &eps0, float &eps1)
 {
     const float L = ln_u1((w0 >> 8) + 1u);
-    const float r = __builtin_sqrtf(-2.0f * L);   // correctly rounded (hipcc default for fp32 sqrt)
+    const float r = sqrt_rn_bounded(-2.0f * L);
     const float f = (float)((w1 >> 6) & 0xFFFFFFu) * 0x1p-24f;
     const float z = f * f;
     float sp = 0x1.3e17cap-13f;
@@ -105,7 +173,7 @@ __device__ __forceinline__ int32_t delta_of(float eps, uint32_t wround, float si
 __device__ __forceinline__ void delta_pair(uint32_t k0, uint32_t k1, uint32_t tensor_id,
                                            uint32_t pair, float sigma, int32_t &d0, int32_t &d1)
 {
-    const Words w = philox4x32_10(pair, 0u, tensor_id, 0u, k0, k1);
+    const Words w = philox_tensor(pair, tensor_id, k0, k1);
     float e0, e1;
     gauss_pair(w.w0, w.w1, e0, e1);
     d0 = delta_of(e0, w.w2, sigma);

@@ -46,6 +46,18 @@ __global__ __launch_bounds__(kBlock) void noise_elems_kernel(uint32_t k0, uint32
     }
 }
 
+__global__ __launch_bounds__(kBlock) void noise_from_words_kernel(const uint4 *__restrict__ words, uint64_t n, float sigma,
+                                                                  float2 *__restrict__ eps2, char2 *__restrict__ delta2)
+{
+    const uint64_t j = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (j >= n) return;
+    const uint4 w = words[j];
+    float g0, g1;
+    gauss_pair(w.x, w.y, g0, g1);
+    if (eps2) eps2[j] = make_float2(g0, g1);
+    if (delta2) delta2[j] = make_char2((signed char)delta_of(g0, w.z, sigma), (signed char)delta_of(g1, w.w, sigma));
+}
+
 template <int MODE>
 __global__ __launch_bounds__(kBlock) void bench_noise_kernel(uint64_t n_threads, int iters, float sigma,
                                                              uint32_t *__restrict__ sink)
@@ -59,7 +71,7 @@ __global__ __launch_bounds__(kBlock) void bench_noise_kernel(uint64_t n_threads,
         const uint32_t k0 = 0x1234567u + (uint32_t)it * 0x9E3779B1u;
         const uint32_t k1 = 0x89ABCDEu ^ (uint32_t)it;
         if (MODE == 0) {
-            const Words w = philox4x32_10(pair, 0u, 7u, 0u, k0, k1);
+            const Words w = philox_tensor(pair, 7u, k0, k1);
             acc ^= w.w0 ^ w.w1 ^ w.w2 ^ w.w3;
         } else {
             int32_t d0, d1;
@@ -105,6 +117,14 @@ hipError_t launch_noise_delta(uint64_t seed, uint32_t tensor_id, uint64_t elem_b
     const uint64_t pairs = ((elem_begin + n + 1) >> 1) - (elem_begin >> 1);
     noise_elems_kernel<1><<<blocks_for(pairs), kBlock, 0, s>>>((uint32_t)seed, (uint32_t)(seed >> 32), tensor_id,
                                                              elem_begin, n, sigma, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_noise_from_words(const uint32_t *words4, uint64_t n, float sigma, float *eps2, int8_t *delta2,
+                                   hipStream_t s)
+{
+    noise_from_words_kernel<<<blocks_for(n), kBlock, 0, s>>>((const uint4 *)words4, n, sigma, (float2 *)eps2,
+                                                           (char2 *)delta2);
     return hipGetLastError();
 }
 

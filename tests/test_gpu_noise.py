@@ -60,3 +60,27 @@ def test_noise_argument_errors(env):
     with pytest.raises(qes.QesError):
         qes.noise_delta(1, 1, 0, 16, float("nan"), out)
     qes.noise_delta(1, 1, 0, 0, 1.0, out)          # empty request is a no-op
+
+
+@pytest.mark.parametrize("sweep", ["radius", "angle"])
+def test_every_radius_and_angle_input(env, sweep):
+    """All 2^24 radius inputs (with a few angle words) and all 2^24 angle fractions (with every
+    quadrant, random radius words): Gaussians and perturbations identical to the oracle's."""
+    torch, qes, oracle = env["torch"], env["qes"], env["oracle"]
+    rng = np.random.default_rng(5)
+    chunk = 1 << 22
+    for c0 in range(0, 1 << 24, chunk):
+        j = np.arange(c0, c0 + chunk, dtype=np.uint64)
+        words = rng.integers(0, 1 << 32, size=(chunk, 4), dtype=np.uint64).astype(np.uint32)
+        if sweep == "radius":
+            words[:, 0] = ((j << 8) | (words[:, 0] & 0xFF)).astype(np.uint32)
+            words[: chunk // 2, 1] = 0
+        else:
+            words[:, 1] = (((j & 3) << 30) | (j << 6) & 0x3FFFFFC0 | (words[:, 1] & 0x3F)).astype(np.uint32)
+        wd = torch.from_numpy(words.view(np.int32)).to(env["DEV"])
+        eps = torch.empty((chunk, 2), dtype=torch.float32, device=env["DEV"])
+        dl = torch.empty((chunk, 2), dtype=torch.int8, device=env["DEV"])
+        qes.noise_from_words(wd, chunk, 1.0, eps, dl)
+        ref_eps, ref_dl = oracle.noise_from_words(words, 1.0)
+        assert (env["from_dev"](eps, np.uint32) == ref_eps.view(np.uint32)).all()
+        assert (env["from_dev"](dl, np.int8) == ref_dl).all()

@@ -183,3 +183,25 @@ def test_delta_window_addressing(oracle):
     full = oracle.noise_delta(5, 2, 0, 4096, 1.0)
     for begin, cnt in [(1, 100), (2, 3), (999, 1001), (4095, 1)]:
         assert (oracle.noise_delta(5, 2, begin, cnt, 1.0) == full[begin:begin + cnt]).all()
+
+
+def test_from_words_matches_generated_stream(oracle):
+    seed, tid, n = 99, 4, 20000
+    w = oracle.noise_words(seed, tid, 0, n)
+    eps, delta = oracle.noise_from_words(w, 1.0)
+    assert (eps.reshape(-1) == oracle.noise_gauss(seed, tid, 0, 2 * n)).all()
+    assert (delta.reshape(-1) == oracle.noise_delta(seed, tid, 0, 2 * n, 1.0)).all()
+
+
+def test_radius_is_correctly_rounded_sqrt_for_every_input(oracle):
+    # eps0 with angle word 0 is r * CP0; sweep a slice of all 2^24 radius inputs and compare r with
+    # the fp64 square root of the oracle's own ln value, rounded once to fp32
+    ms = np.arange(1, (1 << 24) + 1, 257, dtype=np.uint64)
+    words = np.zeros((ms.size, 4), dtype=np.uint32)
+    words[:, 0] = ((ms - 1) << 8).astype(np.uint32)
+    eps, _ = oracle.noise_from_words(words, 1.0)
+    cp0 = np.float32(float.fromhex("0x1.fffffep-1"))
+    L = np.array([oracle.ln_u1(int(m)) for m in ms[::97]], dtype=np.float32)
+    r = np.sqrt((np.float32(-2.0) * L).astype(np.float64)).astype(np.float32)
+    assert (eps[::97, 0] == r * cp0).all()
+    assert (eps[:, 1] == 0).all()                      # sin(0) = 0: the odd lane is r * 0
