@@ -1,0 +1,179 @@
+"""GPU parity on the benchmark configurations themselves (workloads.CONFIGS), through the C ABI.
+
+Configs 1 and 2 run their whole multi-iteration loop in lock step: each ABI call is compared on
+identical inputs, and the fitness vector computed from the GPU's GEMM outputs is fed to both the
+GPU update and the oracle update, so the weights stay bit-identical and the next iteration's GEMM
+is again compared on identical weights. Config 1 is checked in full; config 2 and the big configs
+(3, 4, 5: one full-size layer, real N, T and K, the launch configuration bench.py times) are checked
+on sampled output rows, which the counter-based noise makes exact: first row, last row and seeded
+random rows of every tensor.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env(oracle):
+    import torch
+    import paper_2602_03120_amd as qes
+    import gpu_util
+    assert torch.cuda.is_available()
+    return dict(torch=torch, qes=qes, u=gpu_util, oracle=oracle)
+
+
+def _tensors(env, cfg, layer):
+    oracle, u = env["oracle"], env["u"]
+    out = []
+    for li, spec in enumerate(cfg.linears):
+        ot = oracle.Tensor(wl.make_qweight(cfg, layer, li), wl.make_scales(cfg, layer, li), spec.out_features,
+                           spec.in_features, cfg.bits, cfg.group_size, cfg.qmin, cfg.qmax, cfg.tensor_id(layer, li))
+        out.append((spec, ot, u.device_tensor(ot)))
+    return out
+
+
+def _activations(env, cfg):
+    torch, u = env["torch"], env["u"]
+    xs = {}
+    for spec in cfg.linears:
+        if spec.x_key not in xs:
+            xb = wl.make_activations(cfg, spec.x_key, spec.in_features)
+            xs[spec.x_key] = (xb, u.to_dev(xb).view(torch.bfloat16))
+    return xs
+
+
+def _gemm(env, cfg, dt, seeds, xd, ws):
+    torch, qes, u = env["torch"], env["qes"], env["u"]
+    y = torch.empty((cfg.N, cfg.T, dt.out_features), dtype=torch.bfloat16, device=u.DEV)
+    qes.perturbed_qgemm(dt, seeds, cfg.sigma, xd, y, act_mode=cfg.act_mode, workspace=ws)
+    return y.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _packed_rows(ot, arr, rows):
+    """Rows of a packed weight array (uint8 [out,in/2] or int8 [out,in])."""
+    return arr.reshape(ot.out_features, -1)[rows]
+
+
+@pytest.mark.parametrize("cfg_index,n_random_rows", [(1, None), (2, 64)])
+def test_lock_step_iterations(env, cfg_index, n_random_rows):
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    cfg = wl.CONFIGS[cfg_index]
+    tensors = _tensors(env, cfg, 0)
+    xs = _activations(env, cfg)
+    targets = [wl.bf16_bits_to_f32(wl.make_target(cfg, li)).astype(np.float64) for li in range(len(cfg.linears))]
+    seeds = wl.make_seeds(cfg, cfg.iters)
+    rows = [None if n_random_rows is None else wl.sample_rows(cfg, 0, li, n_random_rows)
+            for li in range(len(cfg.linears))]
+    hist_fit = np.zeros((0, cfg.N), dtype=np.float32)
+    moved = 0
+    for it in range(cfg.iters):
+        # ---- population evaluation: every linear, every member, compared column by column
+        mse = np.zeros(cfg.N)
+        for li, (spec, ot, dt) in enumerate(tensors):
+            xb, xd = xs[spec.x_key]
+            y = _gemm(env, cfg, dt, seeds[it], xd, None)
+            ref = oracle.perturbed_qgemm(ot, seeds[it], cfg.sigma, xb, rows=rows[li])
+            sel = slice(None) if rows[li] is None else rows[li]
+            ok, worst = u.bf16_close(y[:, :, sel], ref[:, :, sel])
+            assert ok, (it, spec.name, worst)
+            yf = wl.bf16_bits_to_f32(y).astype(np.float64)
+            mse += ((yf - targets[li][None]) ** 2).mean(axis=(1, 2))
+        # fitness = -MSE (mean over the layers), z-scored; taken from the GPU outputs for both sides
+        fit = qes.normalize_fitness((-mse / len(tensors)).astype(np.float32))
+        assert (fit == oracle.normalize_fitness((-mse / len(tensors)).astype(np.float32))).all()
+        # ---- update with the history seen so far (window K), both sides
+        lo = max(0, it - cfg.K)
+        for li, (spec, ot, dt) in enumerate(tensors):
+            before = _packed_rows(ot, ot.qweight, slice(None) if rows[li] is None else rows[li]).copy()
+            qes.update(dt, seeds[it], fit, seeds[lo:it], hist_fit[lo:it], cfg.sigma, cfg.alpha, cfg.gamma)
+            oracle.update(ot, seeds[it], fit, seeds[lo:it], hist_fit[lo:it], cfg.sigma, cfg.alpha, cfg.gamma,
+                          rows=rows[li])
+            got = dt.qweight.cpu().numpy()
+            sel = slice(None) if rows[li] is None else rows[li]
+            assert (_packed_rows(ot, got, sel) == _packed_rows(ot, ot.qweight, sel)).all(), (it, spec.name)
+            moved += int((_packed_rows(ot, ot.qweight, sel) != before).sum())
+            if rows[li] is not None:
+                # rows the oracle did not follow take the GPU's values, so the next GEMM sees identical weights
+                ot.qweight[...] = got.reshape(ot.qweight.shape)
+        hist_fit = np.concatenate([hist_fit, fit[None]], axis=0)
+    assert moved > 0
+
+
+@pytest.mark.parametrize("cfg_index", [3, 4, 5])
+def test_full_size_layer_sampled_rows(env, cfg_index):
+    """One full-size layer of the big configurations: every tensor shape with the real N, T and K."""
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    cfg = wl.CONFIGS[cfg_index]
+    seeds = wl.make_seeds(cfg, cfg.K + 1)
+    fits = np.stack([oracle.normalize_fitness(r) for r in wl.make_rewards(cfg, cfg.K + 1)])
+    xs = {}
+    for li, spec in enumerate(cfg.linears):
+        rows = wl.sample_rows(cfg, 0, li, 10)
+        ot = oracle.Tensor(wl.make_qweight(cfg, 0, li), wl.make_scales(cfg, 0, li), spec.out_features,
+                           spec.in_features, cfg.bits, cfg.group_size, cfg.qmin, cfg.qmax, cfg.tensor_id(0, li))
+        dt = u.device_tensor(ot)
+        if spec.x_key not in xs:
+            xs.clear()      # one activation tensor at a time: config 4's are hundreds of MB
+            xb = wl.make_activations(cfg, spec.x_key, spec.in_features)
+            xs[spec.x_key] = (xb, u.to_dev(xb).view(torch.bfloat16))
+        xb, xd = xs[spec.x_key]
+        nbytes = qes.gemm_workspace_bytes(dt, cfg.N, cfg.T, cfg.act_mode)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=u.DEV) if nbytes else None
+        # ---- GEMM, sampled output columns, all members and tokens
+        y = _gemm(env, cfg, dt, seeds[cfg.K], xd, ws)
+        ref = oracle.perturbed_qgemm(ot, seeds[cfg.K], cfg.sigma, xb, act_mode=cfg.act_mode, rows=rows)
+        if cfg.act_mode == 1:
+            assert (y[:, :, rows] == ref[:, :, rows]).all(), spec.name
+        else:
+            ok, worst = u.bf16_close(y[:, :, rows], ref[:, :, rows])
+            assert ok, (spec.name, worst)
+        del ws
+        # ---- replayed residual, sampled rows (fp32, compared exactly)
+        res = torch.empty((spec.out_features, spec.in_features), dtype=torch.float32, device=u.DEV)
+        qes.replay_residual(dt, seeds[:cfg.K], fits[:cfg.K], cfg.N, cfg.sigma, cfg.alpha, cfg.gamma, res)
+        res_rows = res[torch.from_numpy(rows.astype(np.int64)).to(u.DEV)].cpu().numpy()
+        del res
+        ref_res = np.zeros((spec.out_features, spec.in_features), dtype=np.float32)
+        oracle.replay_residual(ot, seeds[:cfg.K], fits[:cfg.K], cfg.N, cfg.sigma, cfg.alpha, cfg.gamma, rows=rows,
+                               residual=ref_res)
+        assert (res_rows.view(np.uint32) == ref_res[rows].view(np.uint32)).all(), spec.name
+        # ---- update with the full window, sampled rows, bit-exact packed weights
+        qes.update(dt, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha, cfg.gamma)
+        oracle.update(ot, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha, cfg.gamma,
+                      rows=rows)
+        got = dt.qweight.cpu().numpy()
+        assert (_packed_rows(ot, got, rows) == _packed_rows(ot, ot.qweight, rows)).all(), spec.name
+        del dt, got, ot
+
+
+def test_maximum_population_and_history(env):
+    """N = 1024 members and hist_len = 256 generations (the ABI's limits) on a small tensor."""
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    N, K = 1024, 256
+    qw, sc, qmin, qmax = wl.random_tensor(77, 8, 64, 4, 32)
+    ot = oracle.Tensor(qw, sc, 8, 64, 4, 32, qmin, qmax, 3)
+    dt = u.device_tensor(ot)
+    rng = np.random.default_rng(123)
+    seeds = rng.integers(0, 2 ** 63, size=(K + 1, N), dtype=np.uint64)
+    fits = np.stack([oracle.normalize_fitness(rng.standard_normal(N).astype(np.float32)) for _ in range(K + 1)])
+    stats = torch.zeros(2, dtype=torch.int64, device=u.DEV)
+    qes.update(dt, seeds[K], fits[K], seeds[:K], fits[:K], 1.0, 8.0, 0.9, stats=stats)
+    ref_stats = oracle.update(ot, seeds[K], fits[K], seeds[:K], fits[:K], 1.0, 8.0, 0.9)
+    assert (dt.qweight.cpu().numpy() == ot.qweight).all()
+    assert (stats.cpu().numpy().view(np.uint64) == ref_stats).all() and ref_stats[0] > 0
+    # one more member or generation than the limit is refused
+    with pytest.raises(qes.QesError):
+        qes.update(dt, np.zeros(N + 1, np.uint64), np.zeros(N + 1, np.float32), None, None, 1.0, 0.5, 0.9)
+    with pytest.raises(qes.QesError):
+        qes.update(dt, seeds[K], fits[K], np.zeros((K + 1, N), np.uint64), np.zeros((K + 1, N), np.float32), 1.0, 0.5,
+                   0.9)
+    # GEMM with 1024 members of one token each
+    x = wl.f32_to_bf16_bits(rng.standard_normal((N, 1, 64)).astype(np.float32))
+    y = torch.empty((N, 1, 8), dtype=torch.bfloat16, device=u.DEV)
+    qes.perturbed_qgemm(dt, seeds[0], 1.0, u.to_dev(x).view(torch.bfloat16), y)
+    ref = oracle.perturbed_qgemm(ot, seeds[0], 1.0, x)
+    ok, worst = u.bf16_close(y.view(torch.int16).cpu().numpy().view(np.uint16), ref)
+    assert ok, worst
