@@ -113,7 +113,8 @@ __device__ __forceinline__ float ln_u1(uint32_t m)
 {
     const float xf = (float)m;
     const uint32_t ix = __float_as_uint(xf) - 0x3F3504F3u;
-    const int32_t e = (int32_t)(ix >> 23) - 24;
+    // float(e - 24) for e = ix >> 23 in [0,24]: 2^23 + e is exact, so is the subtraction
+    const float ef = __uint_as_float((ix >> 23) | 0x4B000000u) - 8388632.0f;
     const float t = __uint_as_float((ix & 0x007FFFFFu) + 0x3F3504F3u) - 1.0f;
     float p = -0x1.a7d988p-4f;
     p = __builtin_fmaf(p, t, 0x1.4d64acp-3f);
@@ -123,7 +124,7 @@ __device__ __forceinline__ float ln_u1(uint32_t m)
     p = __builtin_fmaf(p, t, 0x1.5559f0p-2f);
     p = __builtin_fmaf(p, t, -0x1.000060p-1f);
     const float l1 = __builtin_fmaf(t * t, p, t);
-    return __builtin_fmaf((float)e, 0x1.62e430p-1f, l1);
+    return __builtin_fmaf(ef, 0x1.62e430p-1f, l1);
 }
 
 // N3 + N4. The two standard Gaussians of one Philox call (lane 0: even element, lane 1: odd).
@@ -131,7 +132,7 @@ __device__ __forceinline__ void gauss_pair(uint32_t w0, uint32_t w1, float &eps0
 {
     const float L = ln_u1((w0 >> 8) + 1u);
     const float r = sqrt_rn_bounded(-2.0f * L);
-    const float f = (float)((w1 >> 6) & 0xFFFFFFu) * 0x1p-24f;
+    const float f = (float)(w1 & 0x3FFFFFC0u) * 0x1p-30f;   // = ((w1 >> 6) & 0xFFFFFF) * 2^-24, exact
     const float z = f * f;
     float sp = 0x1.3e17cap-13f;
     sp = __builtin_fmaf(sp, z, -0x1.32535ap-8f);
@@ -167,6 +168,32 @@ __device__ __forceinline__ int32_t delta_of(float eps, uint32_t wround, float si
     d = d < -8 ? -8 : d;
     d = d > 7 ? 7 : d;
     return d;
+}
+
+// N5 + N6 with the result kept in fp32 (every value is a small integer, so this is the same number):
+// saves the two int<->float conversions when the consumer is the fp32 sum of Eq. 5. CLAMP = false
+// is valid when sigma <= 1.2: |sigma*eps| < 7, so the container clamp cannot fire.
+template <bool CLAMP>
+__device__ __forceinline__ float delta_f32(float eps, uint32_t wround, float sigma)
+{
+    const float ub = (float)(wround >> 8) * 0x1p-24f;
+    const float t = sigma * eps;
+    const float fl = __builtin_floorf(t);
+    const float fr = t - fl;
+    float d = fl + ((ub < fr) ? 1.0f : 0.0f);
+    if (CLAMP) d = __builtin_amdgcn_fmed3f(d, -8.0f, 7.0f);
+    return d;
+}
+
+template <bool CLAMP>
+__device__ __forceinline__ void delta_pair_f32(uint32_t k0, uint32_t k1, uint32_t tensor_id, uint32_t pair,
+                                               float sigma, float &d0, float &d1)
+{
+    const Words w = philox_tensor(pair, tensor_id, k0, k1);
+    float e0, e1;
+    gauss_pair(w.w0, w.w1, e0, e1);
+    d0 = delta_f32<CLAMP>(e0, w.w2, sigma);
+    d1 = delta_f32<CLAMP>(e1, w.w3, sigma);
 }
 
 // The two perturbations of pair `pair` (32-bit pair index, high counter word 0) of a tensor.

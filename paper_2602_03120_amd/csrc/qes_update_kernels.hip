@@ -93,7 +93,7 @@ struct Raw {
     }
 };
 
-template <int BITS, int PPT, bool RESIDUAL>
+template <int BITS, int PPT, bool RESIDUAL, bool CLAMP>
 __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
 {
     using P = Pack<BITS>;
@@ -123,10 +123,10 @@ __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
             const float fit = __uint_as_float(en.fit_bits);
 #pragma unroll
             for (int j = 0; j < PPT; ++j) {
-                int32_t d0, d1;
-                delta_pair(en.seed_lo, en.seed_hi, a.tensor_id, pair0 + j, a.sigma, d0, d1);
-                g[2 * j] = __builtin_fmaf(fit, (float)d0, g[2 * j]);
-                g[2 * j + 1] = __builtin_fmaf(fit, (float)d1, g[2 * j + 1]);
+                float d0, d1;
+                delta_pair_f32<CLAMP>(en.seed_lo, en.seed_hi, a.tensor_id, pair0 + j, a.sigma, d0, d1);
+                g[2 * j] = __builtin_fmaf(fit, d0, g[2 * j]);
+                g[2 * j + 1] = __builtin_fmaf(fit, d1, g[2 * j + 1]);
             }
         }
         const bool last = !RESIDUAL && (tau == a.steps - 1);
@@ -179,10 +179,20 @@ hipError_t launch_ppt(const UpdateArgs &a, hipStream_t s)
     while (ppt > 1 && ((a.n_pairs % ppt) != 0 || a.n_pairs / ppt < want_threads)) ppt >>= 1;
     const uint64_t threads = a.n_pairs / ppt;
     const unsigned blocks = (unsigned)((threads + kBlock - 1) / kBlock);
-    switch (ppt) {
-    case 4: update_kernel<BITS, 4, RESIDUAL><<<blocks, kBlock, 0, s>>>(a); break;
-    case 2: update_kernel<BITS, 2, RESIDUAL><<<blocks, kBlock, 0, s>>>(a); break;
-    default: update_kernel<BITS, 1, RESIDUAL><<<blocks, kBlock, 0, s>>>(a); break;
+    // |sigma*eps| <= 1.2 * 5.77 < 7: the 4-bit container clamp cannot fire and is compiled out
+    const bool clamp = !(a.sigma <= 1.2f);
+    if (clamp) {
+        switch (ppt) {
+        case 4: update_kernel<BITS, 4, RESIDUAL, true><<<blocks, kBlock, 0, s>>>(a); break;
+        case 2: update_kernel<BITS, 2, RESIDUAL, true><<<blocks, kBlock, 0, s>>>(a); break;
+        default: update_kernel<BITS, 1, RESIDUAL, true><<<blocks, kBlock, 0, s>>>(a); break;
+        }
+    } else {
+        switch (ppt) {
+        case 4: update_kernel<BITS, 4, RESIDUAL, false><<<blocks, kBlock, 0, s>>>(a); break;
+        case 2: update_kernel<BITS, 2, RESIDUAL, false><<<blocks, kBlock, 0, s>>>(a); break;
+        default: update_kernel<BITS, 1, RESIDUAL, false><<<blocks, kBlock, 0, s>>>(a); break;
+        }
     }
     return hipGetLastError();
 }

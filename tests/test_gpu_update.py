@@ -68,7 +68,8 @@ def test_update_bit_exact(env, bits, out_f, in_f, K, N):
         assert ref_stats[1] > 0                   # and the gate fired (uniform weights sit on edges)
 
 
-@pytest.mark.parametrize("sigma,alpha,gamma", [(1.0, 0.5, 0.9), (0.01, 5e-4, 0.9), (2.5, 3.0, 1.0), (0.7, 0.3, 0.0)])
+@pytest.mark.parametrize("sigma,alpha,gamma", [(1.0, 0.5, 0.9), (0.01, 5e-4, 0.9), (2.5, 3.0, 1.0), (0.7, 0.3, 0.0),
+                                               (1.2, 0.5, 0.9), (1.25, 0.5, 0.9), (4.0, 2.0, 0.9)])
 def test_update_hyperparameters(env, sigma, alpha, gamma):
     oracle = env["oracle"]
     qw, _, qmin, qmax = wl.random_tensor(5, 96, 160, 4, 0)
