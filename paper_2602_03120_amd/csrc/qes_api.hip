@@ -257,6 +257,8 @@ int qes_perturbed_qgemm(const qes_tensor *w, const uint64_t *seeds, const uint8_
     if (act_mode != 0 && act_mode != 1) return QES_ERR_INVALID_ARG;
     if (act_mode == 1 && (w->bits != 8 || w->group_size != 0)) return QES_ERR_INVALID_ARG;
     if ((w->in_features % 32) != 0 || (w->group_size % 32) != 0) return QES_ERR_UNSUPPORTED;
+    // one member's activations are addressed with 32-bit byte offsets inside the kernel
+    if ((uint64_t)T * (uint64_t)w->in_features * 2u >= (1ull << 32)) return QES_ERR_UNSUPPORTED;
     if ((uint64_t)N * (uint64_t)T * (uint64_t)w->in_features >= (1ull << 40)) return QES_ERR_UNSUPPORTED;
     hipStream_t s = (hipStream_t)stream;
 

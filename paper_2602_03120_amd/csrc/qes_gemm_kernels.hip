@@ -3,20 +3,27 @@
 //
 //   Y[i,t,n] = Σ_g s[n,g] · Σ_{k in g} X[i,t,k] · W'_i[n,k],   W'_i = Gate(W + δ_i)
 //
-// Work decomposition. The cost is the regeneration of δ (about sixty vector-ALU operations per
-// weight element and member) against 2·T MFMA flops, so every (member, n, k) draw is generated
-// exactly once: a workgroup owns one member, an n-tile of 16·kWaves output rows and ALL of that
-// member's tokens (up to TM per pass), and walks K. Each wave owns 16 output rows; per k-substep a
-// lane regenerates the K-consecutive elements of its MFMA B fragment in registers, gates them
-// against the base integers and hands them to the matrix core as exact small integers (bf16 or
-// int8).
+// The cost is the regeneration of δ (about sixty vector-ALU operations per weight element and
+// member) against 2·T MFMA flops, so the design goal is that every (member, n, k) draw is generated
+// exactly once and that the noise arithmetic is spread evenly over all waves, with the MFMAs, the
+// LDS traffic and the global loads hidden underneath it.
 //
-// Overlap. The noise of substep s+1 is generated while the MFMAs of substep s execute: the B
-// fragment is double-buffered in registers and the source interleaves one Philox pair with a
-// quarter of the substep's MFMAs and their LDS reads. The activation tile of the next 64-k stage
-// is fetched straight into LDS (global_load_lds_dwordx4, no registers) while the current stage is
-// consumed; LDS is double-buffered and XOR-swizzled so that the b128 fragment reads are
-// conflict-free without padding. One barrier per stage.
+// Decomposition. A workgroup owns one member, RG groups of 16 output rows and ALL tokens of that
+// member (TM per pass). Each row group is served by kTS = 4 waves. Per k-substep (32 k for bf16,
+// 64 k for int8 operands) the MFMA B fragment of a row group is 4 dwords per lane; wave ts
+// regenerates dword ts of it (one or two Philox pairs: draw, gate against the base integers, pack
+// as exact small-integer bf16 or int8), publishes it through LDS, and after the workgroup barrier
+// every wave of the group reads the whole fragment back (one b128) and runs the MFMAs of its own
+// share of the token tiles. So the noise work per wave is a quarter of a fragment whatever the
+// token count, the accumulators per wave are a quarter of the token tiles (high occupancy), and
+// short token counts still use all four waves for noise.
+//
+// Pipelining. B fragments are double-buffered in LDS: the dword for substep s+1 is generated while
+// the MFMAs of substep s run. The activation tile of substep s+1 goes straight from global memory
+// into LDS (global_load_lds_dwordx4, no registers) while substep s is consumed; it is
+// double-buffered in two separate LDS arrays (so the compiler knows reads of one never wait for
+// loads into the other) and XOR-swizzled so the b128 fragment reads are conflict-free without
+// padding. One workgroup barrier per substep.
 //
 // Group scales. The accumulators are kept in units of the current group's scale: at a group
 // boundary they are multiplied by s_old/s_new (one multiply per accumulator) and the integers
@@ -26,6 +33,8 @@
 // MFMA shapes (gfx950): v_mfma_f32_16x16x32_bf16 and v_mfma_i32_16x16x64_i8. Operand layout for a
 // 64-lane wave: A lane l holds row l%16, k-chunk l/16; B lane l holds column l%16, k-chunk l/16;
 // C lane l holds column l%16, rows 4·(l/16)..+3.
+#include <type_traits>
+
 #include "qes_internal.hpp"
 #include "qes_noise.hpp"
 
@@ -39,10 +48,16 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
 
-constexpr int kWaves = 4;
+constexpr int kRG = 4;          // row groups (of 16 output rows) per workgroup
+constexpr int kWaves = 8;       // waves per workgroup
 constexpr int kThreads = kWaves * 64;
-constexpr int kTileN = 16 * kWaves;
-constexpr int kStageK = 64;   // k extent of one LDS stage
+constexpr int kTileN = 16 * kRG;
+constexpr int kWM = 4;          // MFMA blocking: wave (wm, wr) owns token tiles m = wm mod 4 ...
+constexpr int kWR = 2;          // ... of row groups 2*wr and 2*wr+1
+constexpr int kRowBytes = 64;   // one LDS row of the activation tile: 32 bf16 or 64 int8
+constexpr int kFragBytes = kRG * 64 * 16;   // one buffer of B fragments: 16 bytes per lane and row group
+
+enum Mode { kBf16W4 = 0, kBf16W8 = 1, kI8W8 = 2 };
 
 union Frag {
     uint32_t u[4];
@@ -78,19 +93,6 @@ __device__ __forceinline__ bool block_to_work(uint32_t n_tiles, uint32_t n_membe
     return true;
 }
 
-// Base integers of one lane's fragment slice.
-__device__ __forceinline__ void unpack_int4x8(uint32_t word, int32_t w[8])
-{
-#pragma unroll
-    for (int j = 0; j < 8; ++j) w[j] = ((int32_t)(word << (28 - 4 * j))) >> 28;
-}
-
-__device__ __forceinline__ void unpack_int8x4(uint32_t word, int32_t w[4])
-{
-#pragma unroll
-    for (int j = 0; j < 4; ++j) w[j] = ((int32_t)(word << (24 - 8 * j))) >> 24;
-}
-
 // One pair: draw, gate (Eq. 4) in place.
 __device__ __forceinline__ void perturb_pair(int32_t &w0, int32_t &w1, uint32_t k0, uint32_t k1, uint32_t tensor_id,
                                              uint32_t pair, float sigma, int32_t qmin, uint32_t qspan)
@@ -109,410 +111,283 @@ __device__ __forceinline__ uint32_t pack_bf16x2(int32_t a, int32_t b)
     return (lo >> 16) | (hi & 0xFFFF0000u);
 }
 
-__device__ __forceinline__ uint32_t pack_i8x4(const int32_t *w)
+__device__ __forceinline__ uint32_t pack_i8x4(int32_t a, int32_t b, int32_t c, int32_t d)
 {
-    return ((uint32_t)w[0] & 0xFFu) | (((uint32_t)w[1] & 0xFFu) << 8) | (((uint32_t)w[2] & 0xFFu) << 16) |
-           ((uint32_t)w[3] << 24);
+    return ((uint32_t)a & 0xFFu) | (((uint32_t)b & 0xFFu) << 8) | (((uint32_t)c & 0xFFu) << 16) | ((uint32_t)d << 24);
 }
 
-// ------------------------------------------------------------------------------------------------
-// Activation tile -> LDS, asynchronously. ROW_BYTES is 128 (64 bf16) or 64 (64 int8). One wave
-// instruction moves 64 chunks of 16 bytes = 1 KiB of consecutive LDS. A chunk's position inside
-// its row is XOR-swizzled with row bits so that 8 consecutive rows read at the same logical chunk
-// hit 8 different bank groups.
-template <int ROW_BYTES>
-__device__ __forceinline__ int swizzle(int row, int chunk)
-{
-    return ROW_BYTES == 128 ? (chunk ^ (row & 7)) : (chunk ^ ((row >> 2) & 3));
-}
+// Position of logical 16-byte chunk `chunk` (0..3) inside the 64-byte LDS row `row`: XOR-swizzled
+// with row bits 2..3 so that the 16 rows one b128 fragment read touches spread over all banks.
+__device__ __forceinline__ int swizzle(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
 
-template <int TM, int ROW_BYTES, int ELEM_BYTES>
-__device__ __forceinline__ void issue_tile(const char *__restrict__ x_member, int T, int in_features, int t0, int ks,
-                                           char *lds_buf, int wave, int lane)
-{
-    constexpr int kChunksPerRow = ROW_BYTES / 16;
-    constexpr int kRowsPerInstr = 64 / kChunksPerRow;
-    constexpr int kInstr = TM / kRowsPerInstr;
-    constexpr int kElemsPerChunk = 16 / ELEM_BYTES;
-#pragma unroll
-    for (int j = wave; j < kInstr; j += kWaves) {
-        const int row = j * kRowsPerInstr + lane / kChunksPerRow;
-        const int pch = lane % kChunksPerRow;
-        const int ch = swizzle<ROW_BYTES>(row, pch);
-        // rows past T and chunks past in_features are clamped to valid memory; what they deliver is
-        // never used (those outputs are not stored, those substeps are not run)
-        int t = t0 + row;
-        t = t < T ? t : T - 1;
-        int k = ks + ch * kElemsPerChunk;
-        k = k < in_features ? k : in_features - kElemsPerChunk;
-        const char *src = x_member + ((size_t)t * in_features + k) * ELEM_BYTES;
-        __builtin_amdgcn_global_load_lds((gbl_void *)src, (lds_void *)(lds_buf + j * 1024), 16, 0, 0);
-    }
-}
-
-// Slice schedule shared by both GEMM kernels. A substep's MFMA tiles are cut into kSlices slices;
-// slice q's A fragments are read from LDS one slice ahead, then one Philox pair of the NEXT
-// substep's B fragment is generated, then slice q's MFMAs are issued, so LDS latency and MFMA
-// execution both hide behind the noise arithmetic of the same wave. sched_barrier(0) pins that
-// order against the compiler's own scheduling.
-template <int kMT, int kSlices>
-__device__ __forceinline__ constexpr int slice_of(int m)
-{
-    return kMT >= kSlices ? (m * kSlices) / kMT : kSlices - kMT + m;
-}
-template <int kMT, int kSlices>
-constexpr int kSliceTiles = kMT >= kSlices ? (kMT + kSlices - 1) / kSlices : 1;
-
-#define QES_PIN_ORDER() __builtin_amdgcn_sched_barrier(0)
-
-// ------------------------------------------------------------------------------------------------
-// bf16 activations (act_mode 0), INT4 or INT8 weights. TM: tokens per pass (multiple of 16).
-template <int BITS, int TM>
-struct Bf16Gemm {
-    static constexpr int kMT = TM / 16;
-    static constexpr int kTileBytes = TM * 128;
-    static constexpr int kSlices = 4;
-    static constexpr int kST = kSliceTiles<kMT, kSlices>;
+template <int MODE, int TM>
+struct Gemm {
+    static constexpr bool kI8 = (MODE == kI8W8);
+    static constexpr int kSubK = kI8 ? 64 : 32;                // k extent of one substep
+    static constexpr int kElemBytes = kI8 ? 1 : 2;             // activation element
+    static constexpr int kMT = TM / 16;                        // token tiles per pass
+    static constexpr int kMy = (kMT + kWM - 1) / kWM;          // token tiles per wave
+    static constexpr int kTileBytes = TM * kRowBytes;
+    static constexpr int kInstr = TM / 16;                     // wave instructions per activation tile
+    static constexpr int kMyInstr = (kInstr + kWaves - 1) / kWaves;
+    static constexpr int H = kI8 ? 8 : 4;                      // elements in this wave's half fragment
+    static constexpr int kWBytesPerSub = (MODE == kBf16W4) ? 16 : (MODE == kBf16W8 ? 32 : 64);   // weight bytes per row and substep
+    using Acc = typename std::conditional<kI8, i32x4, f32x4>::type;
 
     const GemmArgs &a;
     Entry en;
-    int lane, wave, ln, kc, n, n_ld, gs, n_sub;
-    const uint16_t *scales;
-    const char *xg;
-    const char *wrow;
-    size_t elem_row;
-    // running state of one pass
-    f32x4 acc[kMT];
-    Frag b_cur;
-    float s_cur;
-    bool zero_b;
+    int lane, wave, wm, wr, ln, kc, n_sub;
+    int jrg, jhalf;               // noise job of this wave: half `jhalf` of row group `jrg`'s fragment
+    bool tail;                    // int8 only: in_features % 64 == 32, the last substep is half empty
+    const uint16_t *scales[kWR];  // scale rows of this lane's two MFMA row groups
+    const uint16_t *job_scales;   // scale row of this lane's noise job
+    const char *xg;               // this member's activations
+    const char *wrow_lane;        // this lane's packed base integers of substep 0 (noise job)
+    uint32_t pair0;               // pair index of this lane's half fragment of substep 0
+    uint32_t a_off;               // LDS offset of this lane's A fragment of token tile wm
+    uint32_t frag_rd[kWR];        // LDS offsets of this lane's two B fragments inside a fragment buffer
+    uint32_t frag_wr;             // LDS offset of this lane's half fragment (noise job)
+    char *bfrag;                  // 2 * kFragBytes
+    // per pass
+    uint32_t tile_off[kMyInstr];  // global offset of this lane's 16-byte chunk of substep 0, per instruction
+    Acc acc[kMy][kWR];
+    float s_cur[kWR];
+    bool job_zero;
+    int subs_per_group, subs_to_group_end;
+    int group;
+    uint2 raw_next;               // packed base integers of this wave's half fragment of the next substep
+    uint16_t job_scale_next;      // scale bits of the group after the current one (noise job row) ...
+    uint16_t scale_next[kWR];     // ... and of the two MFMA rows, fetched a whole group ahead
 
-    __device__ __forceinline__ void load_base(int s, int32_t w[8]) const
+    // ---- activation tile of substep s -> LDS buffer, asynchronously. One wave instruction moves
+    // 64 chunks of 16 bytes = 16 rows of 64 bytes = 1 KiB of consecutive LDS. Lane l fills row
+    // l/4 of the instruction's 16 rows, physical chunk l%4, with logical chunk swizzle(row, l%4).
+    // Rows past T are clamped to the last token (their outputs are never stored).
+    __device__ __forceinline__ void prepare_tile_offsets(int t0)
     {
-        const int k = s * 32 + kc * 8;
-        if (BITS == 4) {
-            unpack_int4x8(*(const uint32_t *)(wrow + (k >> 1)), w);
+#pragma unroll
+        for (int i = 0; i < kMyInstr; ++i) {
+            const int j = i * kWaves + wave;
+            const int row = j * 16 + (lane >> 2);
+            int t = t0 + row;
+            t = t < a.T ? t : a.T - 1;
+            tile_off[i] = (uint32_t)(((size_t)t * a.in_features) * kElemBytes) + swizzle(row, lane & 3) * 16;
+        }
+    }
+
+    __device__ __forceinline__ void issue_tile(int s, char *buf) const
+    {
+        const char *sbase = xg + (size_t)s * (kSubK * kElemBytes);   // wave-uniform
+#pragma unroll
+        for (int i = 0; i < kMyInstr; ++i) {
+            const int j = i * kWaves + wave;
+            if (kInstr % kWaves != 0 && j >= kInstr) break;
+            uint32_t off = tile_off[i];
+            if (kI8 && tail && s == n_sub - 1) {
+                // chunks 2 and 3 of the half-empty last substep lie past the row: read chunk 0
+                // instead (in bounds); the fragments they meet are zero
+                const int ch = swizzle(j * 16 + (lane >> 2), lane & 3);
+                if (ch >= 2) off -= ch * 16;
+            }
+            __builtin_amdgcn_global_load_lds((gbl_void *)(sbase + off), (lds_void *)(buf + j * 1024), 16, 0, 0);
+        }
+    }
+
+    // the packed base integers of this wave's half fragment of substep s (2, 4 or 8 bytes), fetched
+    // one substep before they are needed
+    __device__ __forceinline__ uint2 load_raw(int s) const
+    {
+        const char *p = wrow_lane + (size_t)s * kWBytesPerSub;
+        if (kI8 && tail && s == n_sub - 1 && kc >= 2) p -= 32;   // past the row: any valid address, value unused
+        if (MODE == kBf16W4) return make_uint2(*(const uint16_t *)p, 0u);
+        if (MODE == kBf16W8) return make_uint2(*(const uint32_t *)p, 0u);
+        return *(const uint2 *)p;
+    }
+
+    // this wave's half of a B fragment of substep s: draw, gate (Eq. 4), pack as exact small integers
+    template <bool PERTURB>
+    __device__ __forceinline__ uint2 make_half(int s, uint2 raw, bool zero) const
+    {
+        int32_t w[H];
+        if (MODE == kBf16W4) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = ((int32_t)(raw.x << (28 - 4 * j))) >> 28;
+        } else if (MODE == kBf16W8) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = ((int32_t)(raw.x << (24 - 8 * j))) >> 24;
         } else {
-            const uint2 two = *(const uint2 *)(wrow + k);
-            unpack_int8x4(two.x, w);
-            unpack_int8x4(two.y, w + 4);
-        }
-    }
-
-    // Rows m*16+ln share their low bits with ln, so the swizzled chunk does not depend on m: one
-    // per-lane address plus an immediate offset per tile.
-    __device__ __forceinline__ void read_slice(const char *lane_base, int q, Frag (&af)[kST]) const
-    {
-        int i = 0;
 #pragma unroll
-        for (int m = 0; m < kMT; ++m) {
-            if (slice_of<kMT, kSlices>(m) != q) continue;
-            af[i++].v = *(const uint4 *)(lane_base + m * 16 * 128);
-        }
-    }
-
-    __device__ __forceinline__ void mfma_slice(int q, const Frag (&af)[kST])
-    {
-        int i = 0;
-#pragma unroll
-        for (int m = 0; m < kMT; ++m) {
-            if (slice_of<kMT, kSlices>(m) != q) continue;
-            acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i++].bf, b_cur.bf, acc[m], 0, 0, 0);
-        }
-    }
-
-    // Substep s: MFMAs of B fragment b_cur against LDS buffer `buf`, while the B fragment of substep
-    // s+1 is produced (NOISE: with perturbation; otherwise base integers only, if there is a next).
-    template <bool NOISE>
-    __device__ __forceinline__ void substep(const char *buf, int s, bool has_next)
-    {
-        const int sub = s & 1;
-        int32_t wn[8];
-        bool zero_next = zero_b;
-        bool rescale = false;
-        float ratio = 1.0f;
-        if (has_next) {
-            load_base(s + 1, wn);
-            const int k_next = (s + 1) * 32;
-            if ((k_next % gs) == 0) {   // the next substep opens a new group
-                const float s_new = f16_bits_to_f32(scales[k_next / gs]);
-                zero_next = (s_new == 0.0f);
-                if (!zero_next) {
-                    ratio = s_cur / s_new;
-                    s_cur = s_new;
-                    rescale = true;
-                }
+            for (int j = 0; j < 4; ++j) {
+                w[j] = ((int32_t)(raw.x << (24 - 8 * j))) >> 24;
+                w[4 + j] = ((int32_t)(raw.y << (24 - 8 * j))) >> 24;
             }
         }
-        const uint32_t pair_next = (uint32_t)((elem_row + (size_t)(s + 1) * 32 + kc * 8) >> 1);
-
-        const char *lane_base = buf + ln * 128 + swizzle<128>(ln, sub * 4 + kc) * 16;
-        Frag af[2][kST];
-        read_slice(lane_base, 0, af[0]);
-#pragma unroll
-        for (int q = 0; q < kSlices; ++q) {
-            if (q + 1 < kSlices) read_slice(lane_base, q + 1, af[(q + 1) & 1]);
-            QES_PIN_ORDER();
-            if (NOISE)
-                perturb_pair(wn[2 * q], wn[2 * q + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair_next + q, a.sigma,
-                             a.qmin, a.qspan);
-            QES_PIN_ORDER();
-            mfma_slice(q, af[q & 1]);
-        }
-        QES_PIN_ORDER();
-        if (has_next) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) b_cur.u[q] = zero_next ? 0u : pack_bf16x2(wn[2 * q], wn[2 * q + 1]);
-            zero_b = zero_next;
-            if (rescale) {   // new unit for the accumulators before the next group adds to them
-#pragma unroll
-                for (int m = 0; m < kMT; ++m) acc[m] *= ratio;
-            }
-        }
-    }
-
-    // One 64-k stage: consume `rd`, prefetch the next stage's activations into `wr`.
-    template <bool PERTURB>
-    __device__ __forceinline__ void stage(const char *rd, char *wr, int st, int n_stage, int t0)
-    {
-        if (st + 1 < n_stage)
-            issue_tile<TM, 128, 2>(xg, a.T, a.in_features, t0, (st + 1) * kStageK, wr, wave, lane);
-        const int s = 2 * st;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            if (s + h >= n_sub) break;
-            const bool has_next = (s + h + 1) < n_sub;
-            if (PERTURB && has_next) substep<true>(rd, s + h, true);
-            else substep<false>(rd, s + h, has_next);
-        }
-        // the next tile must have landed, and everyone must be done with this one
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-        __syncthreads();
-    }
-
-    template <bool PERTURB>
-    __device__ __forceinline__ void pass(char *lds0, char *lds1, int t0, uint16_t *yg)
-    {
-#pragma unroll
-        for (int m = 0; m < kMT; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // unit of the accumulators: scale of the group being accumulated (1 while that is zero)
-        s_cur = f16_bits_to_f32(scales[0]);
-        zero_b = (s_cur == 0.0f);
-        if (zero_b) s_cur = 1.0f;
-
-        __syncthreads();   // the previous pass has finished reading LDS
-        issue_tile<TM, 128, 2>(xg, a.T, a.in_features, t0, 0, lds0, wave, lane);
-
-        // B fragment of substep 0 (nothing to overlap with yet)
-        int32_t w[8];
-        load_base(0, w);
         if (PERTURB) {
-            const uint32_t pair = (uint32_t)((elem_row + kc * 8) >> 1);
+            const uint32_t pair = pair0 + (uint32_t)s * (kSubK / 2);
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                perturb_pair(w[2 * q], w[2 * q + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair + q, a.sigma, a.qmin,
+            for (int p = 0; p < H / 2; ++p)
+                perturb_pair(w[2 * p], w[2 * p + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair + p, a.sigma, a.qmin,
                              a.qspan);
         }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) b_cur.u[q] = zero_b ? 0u : pack_bf16x2(w[2 * q], w[2 * q + 1]);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-
-        const int n_stage = (n_sub + 1) / 2;
-        for (int st = 0; st < n_stage; st += 2) {
-            stage<PERTURB>(lds0, lds1, st, n_stage, t0);
-            if (st + 1 < n_stage) stage<PERTURB>(lds1, lds0, st + 1, n_stage, t0);
-        }
-
-        if (n < a.out_features) {
-#pragma unroll
-            for (int m = 0; m < kMT; ++m)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int t = t0 + m * 16 + kc * 4 + j;
-                    if (t < a.T) yg[(size_t)t * a.out_features + n] = f32_to_bf16_rne(acc[m][j] * s_cur);
-                }
-        }
+        uint2 d;
+        if (kI8) d = make_uint2(pack_i8x4(w[0], w[1], w[2], w[3]), pack_i8x4(w[H - 4], w[H - 3], w[H - 2], w[H - 1]));
+        else d = make_uint2(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]));
+        if (zero || (kI8 && tail && s == n_sub - 1 && kc >= 2)) d = make_uint2(0u, 0u);
+        return d;
     }
-};
 
-template <int BITS, int TM>
-__global__ __launch_bounds__(kThreads, 2) void gemm_bf16_kernel(const GemmArgs a)
-{
-    using G = Bf16Gemm<BITS, TM>;
-    // two separate arrays (not one array with two halves): the compiler then knows that reads of
-    // one never alias the asynchronous loads into the other and does not wait for them
-    __shared__ __attribute__((aligned(1024))) char lds0[G::kTileBytes];
-    __shared__ __attribute__((aligned(1024))) char lds1[G::kTileBytes];
-
-    uint32_t member, tile;
-    const uint32_t n_tiles = (a.out_features + kTileN - 1) / kTileN;
-    if (!block_to_work(n_tiles, (uint32_t)a.N, member, tile)) return;
-
-    G g{a};
-    g.lane = threadIdx.x & 63;
-    g.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    g.ln = g.lane & 15;        // column of B / C within the wave's 16 rows
-    g.kc = g.lane >> 4;        // k-chunk 0..3
-    g.n = tile * kTileN + g.wave * 16 + g.ln;
-    g.n_ld = g.n < a.out_features ? g.n : a.out_features - 1;   // clamp loads, skip stores
-    g.en = a.entries[member];
-    g.gs = a.group_size > 0 ? a.group_size : a.in_features;
-    g.n_sub = a.in_features / 32;
-    g.scales = (const uint16_t *)a.scales + (size_t)g.n_ld * (a.in_features / g.gs);
-    g.xg = (const char *)a.x + (size_t)member * a.T * a.in_features * 2;
-    g.wrow = (const char *)a.qweight + ((size_t)g.n_ld * a.in_features * BITS) / 8;
-    g.elem_row = (size_t)g.n_ld * a.in_features;
-    uint16_t *yg = (uint16_t *)a.y + (size_t)member * a.T * a.out_features;
-    const bool perturb = (g.en.fit_bits != 0u) && (a.sigma != 0.0f);
-
-    for (int t0 = 0; t0 < a.T; t0 += TM) {
-        if (perturb) g.template pass<true>(lds0, lds1, t0, yg);
-        else g.template pass<false>(lds0, lds1, t0, yg);
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
-// W8A8 (act_mode 1): int8 activations quantised per token by quantize_kernel, int8 MFMA, exact
-// int32 accumulation, Y = bf16(((float)acc · a[t]) · s[n]). One 64-k substep per LDS stage.
-template <int TM>
-struct I8Gemm {
-    static constexpr int kMT = TM / 16;
-    static constexpr int kTileBytes = TM * 64;
-    static constexpr int kSlices = kMT >= 32 ? 16 : 8;   // more, smaller slices keep 512 tokens within 256 VGPRs
-    static constexpr int kSlicesPerPair = kSlices / 8;   // 8 Philox pairs per 64-k fragment
-    static constexpr int kST = kSliceTiles<kMT, kSlices>;
-
-    const GemmArgs &a;
-    Entry en;
-    int lane, wave, ln, kc, n, n_ld, n_sub;
-    const char *xg;
-    const char *wrow;
-    size_t elem_row;
-    i32x4 acc[kMT];
-    Frag b_cur;
-
-    // a lane whose 16-chunk lies past in_features (only when in_features % 64 == 32) feeds zeros
-    __device__ __forceinline__ bool lane_in_range(int s) const { return s * 64 + kc * 16 < a.in_features; }
-    __device__ __forceinline__ int lane_k(int s) const
+    // scales of group g+1, requested when group g opens so that nothing waits for them
+    __device__ __forceinline__ void prefetch_scales(int g)
     {
-        const int k = s * 64 + kc * 16;
-        return k < a.in_features ? k : a.in_features - 16;
-    }
-    __device__ __forceinline__ void load_base(int s, int32_t w[16]) const
-    {
-        const uint4 four = *(const uint4 *)(wrow + lane_k(s));
-        unpack_int8x4(four.x, w);
-        unpack_int8x4(four.y, w + 4);
-        unpack_int8x4(four.z, w + 8);
-        unpack_int8x4(four.w, w + 12);
-    }
-    __device__ __forceinline__ void pack(const int32_t w[16], bool in_range)
-    {
+        if ((g + 1) * subs_per_group < n_sub) {
+            job_scale_next = job_scales[g + 1];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) b_cur.u[q] = in_range ? pack_i8x4(w + 4 * q) : 0u;
-    }
-    __device__ __forceinline__ void read_slice(const char *lane_base, int q, Frag (&af)[kST]) const
-    {
-        int i = 0;
-#pragma unroll
-        for (int m = 0; m < kMT; ++m) {
-            if (slice_of<kMT, kSlices>(m) != q) continue;
-            af[i++].v = *(const uint4 *)(lane_base + m * 16 * 64);
-        }
-    }
-    __device__ __forceinline__ void mfma_slice(int q, const Frag (&af)[kST])
-    {
-        int i = 0;
-#pragma unroll
-        for (int m = 0; m < kMT; ++m) {
-            if (slice_of<kMT, kSlices>(m) != q) continue;
-            acc[m] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[i++].i8, b_cur.i8, acc[m], 0, 0, 0);
+            for (int r = 0; r < kWR; ++r) scale_next[r] = scales[r][g + 1];
         }
     }
 
-    template <bool NOISE>
-    __device__ __forceinline__ void substep(const char *buf, int s, bool has_next)
-    {
-        int32_t wn[16];
-        if (has_next) load_base(s + 1, wn);
-        const uint32_t pair_next = (uint32_t)((elem_row + lane_k(s + 1)) >> 1);
-        const char *lane_base = buf + ln * 64 + swizzle<64>(ln, kc) * 16;
-        Frag af[2][kST];
-        read_slice(lane_base, 0, af[0]);
-#pragma unroll
-        for (int q = 0; q < kSlices; ++q) {
-            if (q + 1 < kSlices) read_slice(lane_base, q + 1, af[(q + 1) & 1]);
-            QES_PIN_ORDER();
-            if (NOISE && (q % kSlicesPerPair) == 0) {
-                const int pq = q / kSlicesPerPair;
-                perturb_pair(wn[2 * pq], wn[2 * pq + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair_next + pq, a.sigma,
-                             a.qmin, a.qspan);
-            }
-            QES_PIN_ORDER();
-            mfma_slice(q, af[q & 1]);
-        }
-        QES_PIN_ORDER();
-        if (has_next) pack(wn, lane_in_range(s + 1));
-    }
-
-    template <bool PERTURB>
-    __device__ __forceinline__ void stage(const char *rd, char *wr, int s, int t0)
+    // ---- one substep: MFMAs of the fragments of substep s on tile buffer `xbuf`, this wave's half
+    // fragment of substep s+1 underneath. PAR is the parity of s: it selects the B-fragment buffer
+    // at compile time.
+    template <bool PERTURB, int PAR>
+    __device__ __forceinline__ void substep(int s, const char *xbuf, char *xbuf_next)
     {
         const bool has_next = (s + 1) < n_sub;
-        if (has_next) issue_tile<TM, 64, 1>(xg, a.T, a.in_features, t0, (s + 1) * 64, wr, wave, lane);
-        if (PERTURB && has_next) substep<true>(rd, s, true);
-        else substep<false>(rd, s, has_next);
+        if (has_next) issue_tile(s + 1, xbuf_next);   // xbuf_next was last read in substep s-1
+        const uint2 raw = raw_next;                   // for substep s+1, fetched during substep s-1
+        if (s + 2 < n_sub) raw_next = load_raw(s + 2);
+
+        Frag b[kWR];
+#pragma unroll
+        for (int r = 0; r < kWR; ++r) b[r].v = *(const uint4 *)(bfrag + PAR * kFragBytes + frag_rd[r]);
+        constexpr int kBatch = kMy < 4 ? kMy : 4;   // A fragments in flight at a time
+        Frag af[kBatch];
+        auto read_batch = [&](int i0) {
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i)
+                if (kMT % kWM == 0 || wm + (i0 + i) * kWM < kMT)
+                    af[i].v = *(const uint4 *)(xbuf + a_off + (i0 + i) * kWM * 16 * kRowBytes);
+        };
+        read_batch(0);
+
+        // half fragment of the next substep; a new scale group may start there (bf16 modes)
+        bool new_group = false;
+        if (has_next) {
+            if (!kI8) {
+                if (--subs_to_group_end == 0) {
+                    subs_to_group_end = subs_per_group;
+                    ++group;
+                    new_group = true;
+                    job_zero = ((job_scale_next & 0x7FFFu) == 0);
+                }
+            }
+            *(uint2 *)(bfrag + (1 - PAR) * kFragBytes + frag_wr) = make_half<PERTURB>(s + 1, raw, job_zero);
+        }
+
+#pragma unroll
+        for (int i0 = 0; i0 < kMy; i0 += kBatch) {
+            if (i0 > 0) read_batch(i0);
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                if (kMT % kWM != 0 && wm + (i0 + i) * kWM >= kMT) continue;
+#pragma unroll
+                for (int r = 0; r < kWR; ++r) {
+                    if constexpr (kI8)
+                        acc[i0 + i][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[i].i8, b[r].i8, acc[i0 + i][r], 0, 0, 0);
+                    else
+                        acc[i0 + i][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i].bf, b[r].bf, acc[i0 + i][r], 0, 0, 0);
+                }
+            }
+        }
+        if constexpr (!kI8) {
+            if (new_group) {
+                // the next substep opens a new group: express the accumulators in its scale (a zero
+                // scale keeps the unit; its fragments are zero)
+#pragma unroll
+                for (int r = 0; r < kWR; ++r) {
+                    const float s_new = f16_bits_to_f32(scale_next[r]);
+                    if (s_new != 0.0f) {
+                        const float ratio = s_cur[r] / s_new;
+                        s_cur[r] = s_new;
+#pragma unroll
+                        for (int i = 0; i < kMy; ++i) acc[i][r] *= ratio;
+                    }
+                }
+                prefetch_scales(group);
+            }
+        }
+
+        // the next tile has landed, the next fragments are published, everyone is done with these
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __syncthreads();
     }
 
     template <bool PERTURB>
-    __device__ __forceinline__ void pass(char *lds0, char *lds1, int t0, uint16_t *yg, const float *xs, float s_n)
+    __device__ __forceinline__ void pass(int t0, int n0, char *x0, char *x1, uint16_t *yg, const float *xs,
+                                         const float (&s_row)[kWR])
     {
 #pragma unroll
-        for (int m = 0; m < kMT; ++m) acc[m] = i32x4{0, 0, 0, 0};
-        __syncthreads();
-        issue_tile<TM, 64, 1>(xg, a.T, a.in_features, t0, 0, lds0, wave, lane);
-        int32_t w[16];
-        load_base(0, w);
-        if (PERTURB) {
-            const uint32_t pair = (uint32_t)((elem_row + lane_k(0)) >> 1);
+        for (int i = 0; i < kMy; ++i)
 #pragma unroll
-            for (int q = 0; q < 8; ++q)
-                perturb_pair(w[2 * q], w[2 * q + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair + q, a.sigma, a.qmin,
-                             a.qspan);
+            for (int r = 0; r < kWR; ++r) acc[i][r] = Acc{0, 0, 0, 0};
+        group = 0;
+        subs_to_group_end = subs_per_group;
+        job_zero = false;
+        if (!kI8) {
+            // unit of the accumulators: scale of the group being accumulated (1 while that is zero)
+#pragma unroll
+            for (int r = 0; r < kWR; ++r) {
+                s_cur[r] = f16_bits_to_f32(scales[r][0]);
+                if (s_cur[r] == 0.0f) s_cur[r] = 1.0f;
+            }
+            job_zero = ((job_scales[0] & 0x7FFFu) == 0);
+            prefetch_scales(0);
         }
-        pack(w, lane_in_range(0));
+        prepare_tile_offsets(t0);
+        __syncthreads();   // the previous pass has finished reading LDS
+        issue_tile(0, x0);
+        raw_next = n_sub > 1 ? load_raw(1) : make_uint2(0u, 0u);
+        *(uint2 *)(bfrag + frag_wr) = make_half<PERTURB>(0, load_raw(0), job_zero);
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
 
         for (int s = 0; s < n_sub; s += 2) {
-            stage<PERTURB>(lds0, lds1, s, t0);
-            if (s + 1 < n_sub) stage<PERTURB>(lds1, lds0, s + 1, t0);
+            substep<PERTURB, 0>(s, x0, x1);
+            if (s + 1 < n_sub) substep<PERTURB, 1>(s + 1, x1, x0);
         }
 
-        if (n < a.out_features) {
 #pragma unroll
-            for (int m = 0; m < kMT; ++m)
+        for (int r = 0; r < kWR; ++r) {
+            const int n = n0 + (wr * kWR + r) * 16 + ln;
+            if (n >= a.out_features) continue;
+#pragma unroll
+            for (int i = 0; i < kMy; ++i) {
+                const int m = wm + i * kWM;
+                if (kMT % kWM != 0 && m >= kMT) continue;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int t = t0 + m * 16 + kc * 4 + j;
                     if (t < a.T) {
-                        const float v = ((float)acc[m][j] * xs[t]) * s_n;
+                        float v;
+                        if constexpr (kI8) v = ((float)acc[i][r][j] * xs[t]) * s_row[r];
+                        else v = acc[i][r][j] * s_cur[r];
                         yg[(size_t)t * a.out_features + n] = f32_to_bf16_rne(v);
                     }
                 }
+            }
         }
     }
 };
 
-template <int TM>
-__global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmArgs a)
+template <int MODE, int TM>
+__global__ __launch_bounds__(kThreads, (TM >= 512 ? 4 : 1)) void gemm_kernel(const GemmArgs a)
 {
-    using G = I8Gemm<TM>;
-    __shared__ __attribute__((aligned(1024))) char lds0[G::kTileBytes];
-    __shared__ __attribute__((aligned(1024))) char lds1[G::kTileBytes];
+    using G = Gemm<MODE, TM>;
+    // separate arrays, not halves of one: reads of one tile buffer must not wait for the
+    // asynchronous loads into the other, and the compiler tells them apart per LDS variable
+    __shared__ __attribute__((aligned(1024))) char x0[G::kTileBytes];
+    __shared__ __attribute__((aligned(1024))) char x1[G::kTileBytes];
+    __shared__ __attribute__((aligned(16))) char bfrag[2 * kFragBytes];
 
     uint32_t member, tile;
     const uint32_t n_tiles = (a.out_features + kTileN - 1) / kTileN;
@@ -521,23 +396,46 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmArgs a)
     G g{a};
     g.lane = threadIdx.x & 63;
     g.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    g.ln = g.lane & 15;
-    g.kc = g.lane >> 4;
-    g.n = tile * kTileN + g.wave * 16 + g.ln;
-    g.n_ld = g.n < a.out_features ? g.n : a.out_features - 1;
+    g.wm = g.wave % kWM;
+    g.wr = g.wave / kWM;
+    g.jrg = g.wave >> 1;
+    g.jhalf = g.wave & 1;
+    g.ln = g.lane & 15;        // column of B / C within a row group
+    g.kc = g.lane >> 4;        // k-chunk 0..3
+    const int n0 = tile * kTileN;
+    auto clamp_row = [&](int n) { return n < a.out_features ? n : a.out_features - 1; };   // clamp loads, skip stores
     g.en = a.entries[member];
-    g.n_sub = (a.in_features + 63) / 64;
-    g.xg = (const char *)a.x + (size_t)member * a.T * a.in_features;
-    g.wrow = (const char *)a.qweight + (size_t)g.n_ld * a.in_features;
-    g.elem_row = (size_t)g.n_ld * a.in_features;
-    const float *xs = a.x_scale + (size_t)member * a.T;
+    const int gs = a.group_size > 0 ? a.group_size : a.in_features;
+    const int groups_per_row = a.in_features / gs;
+    g.n_sub = (a.in_features + G::kSubK - 1) / G::kSubK;
+    g.tail = G::kI8 && (a.in_features % 64) != 0;
+    g.subs_per_group = gs / G::kSubK;            // bf16 modes: group_size is a multiple of 32
+    float s_row[kWR];
+#pragma unroll
+    for (int r = 0; r < kWR; ++r) {
+        const int n = clamp_row(n0 + (g.wr * kWR + r) * 16 + g.ln);
+        g.scales[r] = (const uint16_t *)a.scales + (size_t)n * groups_per_row;
+        s_row[r] = G::kI8 ? f16_bits_to_f32(((const uint16_t *)a.scales)[n]) : 1.0f;
+        g.frag_rd[r] = (g.wr * kWR + r) * 1024 + g.lane * 16;
+    }
+    g.xg = (const char *)a.x + (size_t)member * a.T * a.in_features * G::kElemBytes;
+    // noise job: half `jhalf` of row group jrg: elements k0 .. k0+H-1, k0 = s*kSubK + kc*(kSubK/4) + jhalf*H
+    const int jn = clamp_row(n0 + g.jrg * 16 + g.ln);
+    const int k0 = g.kc * (G::kSubK / 4) + g.jhalf * G::H;
+    const size_t elem0 = (size_t)jn * a.in_features + k0;
+    g.job_scales = (const uint16_t *)a.scales + (size_t)jn * groups_per_row;
+    g.wrow_lane = (const char *)a.qweight + (MODE == kBf16W4 ? (elem0 >> 1) : elem0);
+    g.pair0 = (uint32_t)(elem0 >> 1);
+    g.frag_wr = g.jrg * 1024 + g.lane * 16 + g.jhalf * 8;
+    g.a_off = (g.wm * 16 + g.ln) * kRowBytes + swizzle(g.ln, g.kc) * 16;
+    g.bfrag = bfrag;
     uint16_t *yg = (uint16_t *)a.y + (size_t)member * a.T * a.out_features;
-    const float s_n = f16_bits_to_f32(((const uint16_t *)a.scales)[g.n_ld]);
+    const float *xs = G::kI8 ? a.x_scale + (size_t)member * a.T : nullptr;
     const bool perturb = (g.en.fit_bits != 0u) && (a.sigma != 0.0f);
 
     for (int t0 = 0; t0 < a.T; t0 += TM) {
-        if (perturb) g.template pass<true>(lds0, lds1, t0, yg, xs, s_n);
-        else g.template pass<false>(lds0, lds1, t0, yg, xs, s_n);
+        if (perturb) g.template pass<true>(t0, n0, x0, x1, yg, xs, s_row);
+        else g.template pass<false>(t0, n0, x0, x1, yg, xs, s_row);
     }
 }
 
@@ -565,14 +463,24 @@ __global__ __launch_bounds__(256) void quantize_kernel(const uint16_t *__restric
     }
 }
 
-template <int BITS>
-hipError_t launch_bf16(const GemmArgs &a, unsigned blocks, hipStream_t s)
+template <int MODE, int TM>
+void launch_one(const GemmArgs &a, hipStream_t s)
 {
-    if (a.T <= 16) gemm_bf16_kernel<BITS, 16><<<blocks, kThreads, 0, s>>>(a);
-    else if (a.T <= 32) gemm_bf16_kernel<BITS, 32><<<blocks, kThreads, 0, s>>>(a);
-    else if (a.T <= 64) gemm_bf16_kernel<BITS, 64><<<blocks, kThreads, 0, s>>>(a);
-    else if (a.T <= 128) gemm_bf16_kernel<BITS, 128><<<blocks, kThreads, 0, s>>>(a);
-    else gemm_bf16_kernel<BITS, 256><<<blocks, kThreads, 0, s>>>(a);
+    const uint32_t n_tiles = (a.out_features + kTileN - 1) / kTileN;
+    const uint32_t total = n_tiles * (uint32_t)a.N;
+    const unsigned blocks = ((total + 7u) / 8u) * 8u;
+    gemm_kernel<MODE, TM><<<blocks, kThreads, 0, s>>>(a);
+}
+
+template <int MODE>
+hipError_t launch_mode(const GemmArgs &a, hipStream_t s)
+{
+    if (a.T <= 16) launch_one<MODE, 16>(a, s);
+    else if (a.T <= 32) launch_one<MODE, 32>(a, s);
+    else if (a.T <= 64) launch_one<MODE, 64>(a, s);
+    else if (a.T <= 128) launch_one<MODE, 128>(a, s);
+    else if (a.T <= 256) launch_one<MODE, 256>(a, s);
+    else launch_one<MODE, 512>(a, s);
     return hipGetLastError();
 }
 
@@ -589,17 +497,8 @@ hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_
 
 hipError_t launch_gemm(const GemmArgs &a, int bits, int act_mode, hipStream_t s)
 {
-    const uint32_t n_tiles = (a.out_features + kTileN - 1) / kTileN;
-    const uint32_t total = n_tiles * (uint32_t)a.N;
-    const unsigned blocks = ((total + 7u) / 8u) * 8u;
-    if (act_mode == 1) {
-        if (a.T <= 64) gemm_i8_kernel<64><<<blocks, kThreads, 0, s>>>(a);
-        else if (a.T <= 128) gemm_i8_kernel<128><<<blocks, kThreads, 0, s>>>(a);
-        else if (a.T <= 256) gemm_i8_kernel<256><<<blocks, kThreads, 0, s>>>(a);
-        else gemm_i8_kernel<512><<<blocks, kThreads, 0, s>>>(a);
-        return hipGetLastError();
-    }
-    return bits == 4 ? launch_bf16<4>(a, blocks, s) : launch_bf16<8>(a, blocks, s);
+    if (act_mode == 1) return launch_mode<kI8W8>(a, s);
+    return bits == 4 ? launch_mode<kBf16W4>(a, s) : launch_mode<kBf16W8>(a, s);
 }
 
 }  // namespace qes
