@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--config", type=int, default=2, choices=sorted(wl.CONFIGS))
     ap.add_argument("--layers", type=int, default=None, help="limit the number of layers (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--antithetic", action="store_true",
+                    help="members come in +δ/-δ pairs sharing a seed (App. A.1); not the headline setting")
     return ap.parse_args()
 
 
@@ -104,7 +106,11 @@ def main():
     del copy_src, copy_dst
 
     total_steps = steps + warmup
-    seeds = wl.make_seeds(cfg, cfg.K + total_steps)
+    anti = args.antithetic
+    if anti and cfg.N % 2:
+        print("bench.py: --antithetic needs an even population", file=sys.stderr)
+        sys.exit(2)
+    seeds = wl.make_seeds(cfg, cfg.K + total_steps, cfg.N // 2 if anti else cfg.N)
     rewards = wl.make_rewards(cfg, cfg.K + total_steps)
     fits = np.stack([qes.normalize_fitness(r) for r in rewards])
 
@@ -118,7 +124,7 @@ def main():
         for layer, li, t in tensors:
             spec = cfg.linears[li]
             qes.perturbed_qgemm(t, seeds[cfg.K + s], cfg.sigma, xs[spec.x_key], ys[spec.out_features],
-                                act_mode=cfg.act_mode, workspace=ws)
+                                act_mode=cfg.act_mode, workspace=ws, antithetic=anti)
         g1.record()
         # seeded update with a full replay window (steady state: K generations of history)
         h0 = s
@@ -126,7 +132,7 @@ def main():
             u0, u1 = ev(), ev()
             u0.record()
             qes.update(t, seeds[cfg.K + s], fits[cfg.K + s], seeds[h0:h0 + cfg.K], fits[h0:h0 + cfg.K],
-                       cfg.sigma, cfg.alpha, cfg.gamma, stats=stats)
+                       cfg.sigma, cfg.alpha, cfg.gamma, stats=stats, antithetic=anti)
             u1.record()
             if timed:
                 upd_events.append((li, u0, u1))
@@ -159,12 +165,12 @@ def main():
     dom = cfg.linears[dom_li]
     dom_ms = float(np.mean(upd_ms_by_li[dom_li]))
     dom_elems = dom.out_features * dom.in_features
-    ops = dom_elems * update_ops_per_element(cfg.N, cfg.K + 1)
+    ops = dom_elems * update_ops_per_element(cfg.N // 2 if anti else cfg.N, cfg.K + 1)
     achieved_tops = ops / (dom_ms * 1e-3) / 1e12
     upd_ms_total = float(sum(np.mean(v) for v in upd_ms_by_li.values())) * n_layers
     bytes_per_param = cfg.bits / 8.0 * 2.0          # packed W read + written
     upd_gbps = params * bytes_per_param / (upd_ms_total * 1e-3) / 1e9
-    upd_draws = params * (cfg.K + 1) * cfg.N
+    upd_draws = params * (cfg.K + 1) * (cfg.N // 2 if anti else cfg.N)
 
     out = {
         "metric": "member-tokens/s",
@@ -182,7 +188,8 @@ def main():
         "config": {"workload": "config %d: %s (%d layers of %s), N=%d, T=%d, K=%d, sigma=%g, alpha=%g, gamma=%g"
                    % (cfg.index, cfg.name, n_layers, "/".join(l.name for l in cfg.linears), cfg.N, cfg.T, cfg.K,
                       cfg.sigma, cfg.alpha, cfg.gamma),
-                   "parameters": params, "step": "perturbed qGEMM of every linear + update with full replay window"},
+                   "parameters": params, "step": "perturbed qGEMM of every linear + update with full replay window",
+                   "antithetic_pairs": bool(anti)},
         "roofline": {
             "kernel": "update_kernel (qes_update, %s %dx%d)" % (dom.name, dom.out_features, dom.in_features),
             "bound": "alu", "achieved": achieved_tops, "peak": VALU_PEAK_TOPS, "unit": "Tlane-op/s",
@@ -207,7 +214,7 @@ def main():
         },
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not anti:
         out["cpu_baseline"] = cpu_baseline(cfg, member_tokens)
     print(json.dumps(out))
 

@@ -130,6 +130,16 @@ int qes_perturbed_qgemm(const qes_tensor *w, const uint64_t *seeds, const uint8_
                         int32_t N, float sigma, const void *x, int32_t T, void *y, int32_t act_mode,
                         void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The same with antithetic perturbation pairs (App. A.1: "antithetic perturbation pairs"): N is
+ * even, pair_seeds is HOST uint64 [N/2], members 2j and 2j+1 share pair_seeds[j], member 2j is
+ * evaluated on Gate(W + δ_j) and member 2j+1 on Gate(W − δ_j). x, y and perturb_mask stay per
+ * member. This entry point regenerates δ_j once per member (same results as sharing the draw).
+ */
+int qes_perturbed_qgemm_antithetic(const qes_tensor *w, const uint64_t *pair_seeds, const uint8_t *perturb_mask,
+                                   int32_t N, float sigma, const void *x, int32_t T, void *y, int32_t act_mode,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
 /* Bytes of DEVICE workspace qes_perturbed_qgemm needs for these arguments (0 for act_mode 0). */
 size_t qes_gemm_workspace_bytes(const qes_tensor *w, int32_t N, int32_t T, int32_t act_mode);
 
@@ -165,6 +175,21 @@ int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const
 int qes_replay_residual(const qes_tensor *w, const uint64_t *hist_seeds, const float *hist_fit,
                         int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
                         float *residual, void *stream);
+
+/*
+ * qes_update / qes_replay_residual with antithetic perturbation pairs (App. A.1): N is even; every
+ * generation has N/2 seeds (pair_seeds_t: HOST [N/2]; hist_pair_seeds: HOST [hist_len][N/2]) and N
+ * fitnesses (fit_t: HOST [N]; hist_fit: HOST [hist_len][N]), members 2j and 2j+1 adjacent. Eq. 5 is
+ * summed in member order with δ_{2j+1} = −δ_{2j}, c = α/(Nσ) with N the number of members; one
+ * draw serves both members of a pair, so the noise work is half that of qes_update at equal N.
+ */
+int qes_update_antithetic(qes_tensor *w, const uint64_t *pair_seeds_t, const float *fit_t,
+                          const uint64_t *hist_pair_seeds, const float *hist_fit, int32_t hist_len, int32_t N,
+                          float sigma, float alpha, float gamma, uint64_t *stats, void *stream);
+
+int qes_replay_residual_antithetic(const qes_tensor *w, const uint64_t *hist_pair_seeds, const float *hist_fit,
+                                   int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
+                                   float *residual, void *stream);
 
 /*
  * Alg. 1 "normalize reward for population": z-score with the population standard deviation,

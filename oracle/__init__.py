@@ -52,17 +52,17 @@ def lib():
         L.oracle_noise_from_words.restype = None
         L.oracle_delta_from_gauss.argtypes = [f32, u32, f32]
         L.oracle_delta_from_gauss.restype = i32
-        L.oracle_perturbed_qgemm.argtypes = [tp, vp, vp, i32, f32, vp, i32, vp, i32, vp, i32]
+        L.oracle_perturbed_qgemm.argtypes = [tp, vp, vp, i32, f32, vp, i32, vp, i32, vp, i32, i32]
         L.oracle_perturbed_qgemm.restype = i32
         L.oracle_normalize_fitness.argtypes = [vp, i32, vp]
         L.oracle_normalize_fitness.restype = i32
-        L.oracle_replay_residual.argtypes = [tp, vp, vp, i32, i32, f32, f32, f32, vp, vp, i32]
+        L.oracle_replay_residual.argtypes = [tp, vp, vp, i32, i32, f32, f32, f32, vp, vp, i32, i32]
         L.oracle_replay_residual.restype = i32
-        L.oracle_update.argtypes = [tp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp, i32]
+        L.oracle_update.argtypes = [tp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp, i32, i32]
         L.oracle_update.restype = i32
         L.oracle_update_full_residual.argtypes = [tp, vp, vp, i32, f32, f32, f32, vp, vp, vp]
         L.oracle_update_full_residual.restype = i32
-        L.oracle_aggregate.argtypes = [tp, vp, vp, i32, f32, vp]
+        L.oracle_aggregate.argtypes = [tp, vp, vp, i32, f32, vp, i32]
         L.oracle_aggregate.restype = i32
         _LIB = L
     return _LIB
@@ -177,19 +177,20 @@ def _rows(rows):
     return r, int(r.size)
 
 
-def perturbed_qgemm(w, seeds, sigma, x, act_mode=0, perturb_mask=None, rows=None, y=None):
-    """x: uint16 bf16 bits [N,T,in] -> y: uint16 bf16 bits [N,T,out] (only `rows` columns written)."""
+def perturbed_qgemm(w, seeds, sigma, x, act_mode=0, perturb_mask=None, rows=None, y=None, antithetic=False):
+    """x: uint16 bf16 bits [N,T,in] -> y: uint16 bf16 bits [N,T,out] (only `rows` columns written).
+    antithetic: seeds has N/2 entries; members 2j, 2j+1 use +δ_j, -δ_j."""
     seeds = _c(seeds, np.uint64)
     x = _c(x, np.uint16)
     N, T, K = x.shape
-    assert K == w.in_features and seeds.size == N
+    assert K == w.in_features and seeds.size == (N // 2 if antithetic else N)
     if y is None:
         y = np.zeros((N, T, w.out_features), dtype=np.uint16)
     mask = None if perturb_mask is None else _c(perturb_mask, np.uint8)
     r, nr = _rows(rows)
     d = w.desc()
     _check(lib().oracle_perturbed_qgemm(ctypes.byref(d), _ptr(seeds), _ptr(mask), N, sigma, _ptr(x),
-                                        T, _ptr(y), act_mode, _ptr(r), nr))
+                                        T, _ptr(y), act_mode, _ptr(r), nr, int(antithetic)))
     return y
 
 
@@ -200,38 +201,40 @@ def normalize_fitness(reward):
     return fit
 
 
-def _hist(hist_seeds, hist_fit, N):
+def _hist(hist_seeds, hist_fit, N, antithetic=False):
     if hist_seeds is None or len(hist_seeds) == 0:
         return None, None, 0
-    hs = _c(hist_seeds, np.uint64).reshape(-1, N)
+    hs = _c(hist_seeds, np.uint64).reshape(-1, N // 2 if antithetic else N)
     hf = _c(hist_fit, np.float32).reshape(-1, N)
-    assert hs.shape == hf.shape
+    assert hs.shape[0] == hf.shape[0]
     return hs, hf, hs.shape[0]
 
 
-def replay_residual(w, hist_seeds, hist_fit, N, sigma, alpha, gamma, rows=None, residual=None):
-    hs, hf, hl = _hist(hist_seeds, hist_fit, N)
+def replay_residual(w, hist_seeds, hist_fit, N, sigma, alpha, gamma, rows=None, residual=None, antithetic=False):
+    hs, hf, hl = _hist(hist_seeds, hist_fit, N, antithetic)
     if residual is None:
         residual = np.zeros((w.out_features, w.in_features), dtype=np.float32)
     r, nr = _rows(rows)
     d = w.desc()
     _check(lib().oracle_replay_residual(ctypes.byref(d), _ptr(hs), _ptr(hf), hl, N, sigma, alpha,
-                                        gamma, _ptr(residual), _ptr(r), nr))
+                                        gamma, _ptr(residual), _ptr(r), nr, int(antithetic)))
     return residual
 
 
-def update(w, seeds_t, fit_t, hist_seeds, hist_fit, sigma, alpha, gamma, rows=None, stats=None):
-    """In-place Alg. 2 on w.qweight. Returns stats (uint64[2]: changed, gated) accumulated."""
+def update(w, seeds_t, fit_t, hist_seeds, hist_fit, sigma, alpha, gamma, rows=None, stats=None, antithetic=False):
+    """In-place Alg. 2 on w.qweight. Returns stats (uint64[2]: changed, gated) accumulated.
+    antithetic: seeds arrays hold one seed per pair (N/2 per generation), fitnesses one per member."""
     seeds_t = _c(seeds_t, np.uint64)
     fit_t = _c(fit_t, np.float32)
-    N = seeds_t.size
-    hs, hf, hl = _hist(hist_seeds, hist_fit, N)
+    N = fit_t.size
+    assert seeds_t.size == (N // 2 if antithetic else N)
+    hs, hf, hl = _hist(hist_seeds, hist_fit, N, antithetic)
     if stats is None:
         stats = np.zeros(2, dtype=np.uint64)
     r, nr = _rows(rows)
     d = w.desc()
     _check(lib().oracle_update(ctypes.byref(d), _ptr(seeds_t), _ptr(fit_t), _ptr(hs), _ptr(hf), hl, N,
-                               sigma, alpha, gamma, _ptr(stats), _ptr(r), nr))
+                               sigma, alpha, gamma, _ptr(stats), _ptr(r), nr, int(antithetic)))
     return stats
 
 
@@ -250,10 +253,11 @@ def update_full_residual(w, seeds_t, fit_t, sigma, alpha, gamma, e_state, want_u
     return u, stats
 
 
-def aggregate(w, seeds, fit, sigma):
+def aggregate(w, seeds, fit, sigma, antithetic=False):
     seeds = _c(seeds, np.uint64)
     fit = _c(fit, np.float32)
+    assert seeds.size == (fit.size // 2 if antithetic else fit.size)
     g = np.empty((w.out_features, w.in_features), dtype=np.float32)
     d = w.desc()
-    _check(lib().oracle_aggregate(ctypes.byref(d), _ptr(seeds), _ptr(fit), seeds.size, sigma, _ptr(g)))
+    _check(lib().oracle_aggregate(ctypes.byref(d), _ptr(seeds), _ptr(fit), fit.size, sigma, _ptr(g), int(antithetic)))
     return g

@@ -327,11 +327,14 @@ static double scale_of(const oracle_tensor *w, int64_t row, int64_t col)
  * act_mode 0: bf16 activations, fp64 accumulation of s[n,g]·Σ_k X·W'.
  * act_mode 1 (bits=8, per-row scale): dynamic symmetric per-token int8 activations, exact int32
  * accumulation, Y = bf16(((float)acc·a[t])·(float)s[n]).
+ * antithetic != 0 (App. A.1, "antithetic perturbation pairs"): N is even, seeds has N/2 entries,
+ * members 2j and 2j+1 share seed j and member 2j+1 uses the negated perturbation -δ_j.
  */
 int oracle_perturbed_qgemm(const oracle_tensor *w, const uint64_t *seeds, const uint8_t *perturb_mask,
                            int32_t N, float sigma, const uint16_t *x, int32_t T, uint16_t *y,
-                           int32_t act_mode, const int32_t *rows, int32_t n_rows)
+                           int32_t act_mode, const int32_t *rows, int32_t n_rows, int32_t antithetic)
 {
+    if (antithetic && (N & 1)) return ORACLE_ERR_INVALID_ARG;
     if (!tensor_ok(w) || !w->scales || !seeds || !x || !y || N <= 0 || T <= 0) return ORACLE_ERR_INVALID_ARG;
     if (!(sigma >= 0.0f)) return ORACLE_ERR_INVALID_ARG;
     if (act_mode != 0 && act_mode != 1) return ORACLE_ERR_INVALID_ARG;
@@ -374,8 +377,10 @@ int oracle_perturbed_qgemm(const oracle_tensor *w, const uint64_t *seeds, const 
                 /* this member's perturbed, gated row (Eq. 3, Eq. 4) */
                 for (int64_t k = 0; k < K; k += 2) {
                     int32_t d[2] = { 0, 0 };
-                    if (!perturb_mask || perturb_mask[i])
-                        pair_deltas(seeds[i], w->tensor_id, (uint64_t)(n * K + k) >> 1, sigma, d);
+                    if (!perturb_mask || perturb_mask[i]) {
+                        pair_deltas(seeds[antithetic ? i / 2 : i], w->tensor_id, (uint64_t)(n * K + k) >> 1, sigma, d);
+                        if (antithetic && (i & 1)) { d[0] = -d[0]; d[1] = -d[1]; }
+                    }
                     for (int l = 0; l < 2; ++l) {
                         int32_t q = load_q(w, n, k + l);
                         int32_t v = q + d[l];
@@ -438,13 +443,15 @@ static float step_coeff(float alpha, int32_t N, float sigma)
 
 /* Eq. 5: g = Σ_i F_i δ_i for the two elements of one pair, members in index order, fp32 fma chain */
 static void aggregate_pair(const uint64_t *seeds, const float *fit, int32_t N, uint32_t tensor_id,
-                           uint64_t pair, float sigma, float g[2])
+                           uint64_t pair, float sigma, int32_t antithetic, float g[2])
 {
     g[0] = 0.0f;
     g[1] = 0.0f;
     for (int32_t i = 0; i < N; ++i) {
         int32_t d[2];
-        pair_deltas(seeds[i], tensor_id, pair, sigma, d);
+        /* antithetic pairs: members 2j and 2j+1 share seed j; the odd member's δ is negated */
+        pair_deltas(seeds[antithetic ? i / 2 : i], tensor_id, pair, sigma, d);
+        if (antithetic && (i & 1)) { d[0] = -d[0]; d[1] = -d[1]; }
         g[0] = fmaf(fit[i], (float)d[0], g[0]);
         g[1] = fmaf(fit[i], (float)d[1], g[1]);
     }
@@ -486,14 +493,15 @@ static int hist_ok(const uint64_t *hs, const float *hf, int32_t hist_len, int32_
  * history, oldest first, gating every simulated step against the current weights wq[]. */
 static void replay_pair(const oracle_tensor *w, const uint64_t *hist_seeds, const float *hist_fit,
                         int32_t hist_len, int32_t N, float sigma, float c, float gamma,
-                        uint64_t pair, const int32_t wq[2], float res[2])
+                        uint64_t pair, const int32_t wq[2], int32_t antithetic, float res[2])
 {
+    const int64_t seeds_per_gen = antithetic ? N / 2 : N;
     res[0] = 0.0f;
     res[1] = 0.0f;
     for (int32_t tau = 0; tau < hist_len; ++tau) {
         float g[2];
-        aggregate_pair(hist_seeds + (int64_t)tau * N, hist_fit + (int64_t)tau * N, N, w->tensor_id,
-                       pair, sigma, g);
+        aggregate_pair(hist_seeds + (int64_t)tau * seeds_per_gen, hist_fit + (int64_t)tau * N, N, w->tensor_id,
+                       pair, sigma, antithetic, g);
         for (int l = 0; l < 2; ++l) {
             float u;
             int32_t df = ef_step(c, g[l], gamma, res[l], wq[l], w->qmin, w->qmax, &u, NULL);
@@ -508,10 +516,11 @@ static void replay_pair(const oracle_tensor *w, const uint64_t *hist_seeds, cons
  */
 int oracle_replay_residual(const oracle_tensor *w, const uint64_t *hist_seeds, const float *hist_fit,
                            int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
-                           float *residual, const int32_t *rows, int32_t n_rows)
+                           float *residual, const int32_t *rows, int32_t n_rows, int32_t antithetic)
 {
     if (!tensor_ok(w) || !residual || !hist_ok(hist_seeds, hist_fit, hist_len, N, sigma))
         return ORACLE_ERR_INVALID_ARG;
+    if (antithetic && (N & 1)) return ORACLE_ERR_INVALID_ARG;
     const int64_t K = w->in_features;
     const int32_t nsel = rows ? n_rows : w->out_features;
     const float c = step_coeff(alpha, N, sigma);
@@ -522,7 +531,7 @@ int oracle_replay_residual(const oracle_tensor *w, const uint64_t *hist_seeds, c
             const int32_t wq[2] = { load_q(w, n, k), load_q(w, n, k + 1) };
             float res[2];
             replay_pair(w, hist_seeds, hist_fit, hist_len, N, sigma, c, gamma,
-                        (uint64_t)(n * K + k) >> 1, wq, res);
+                        (uint64_t)(n * K + k) >> 1, wq, antithetic, res);
             residual[n * K + k] = res[0];
             residual[n * K + k + 1] = res[1];
         }
@@ -538,10 +547,11 @@ int oracle_replay_residual(const oracle_tensor *w, const uint64_t *hist_seeds, c
 int oracle_update(oracle_tensor *w, const uint64_t *seeds_t, const float *fit_t,
                   const uint64_t *hist_seeds, const float *hist_fit, int32_t hist_len, int32_t N,
                   float sigma, float alpha, float gamma, uint64_t *stats,
-                  const int32_t *rows, int32_t n_rows)
+                  const int32_t *rows, int32_t n_rows, int32_t antithetic)
 {
     if (!tensor_ok(w) || !seeds_t || !fit_t || !hist_ok(hist_seeds, hist_fit, hist_len, N, sigma))
         return ORACLE_ERR_INVALID_ARG;
+    if (antithetic && (N & 1)) return ORACLE_ERR_INVALID_ARG;
     const int64_t K = w->in_features;
     const int32_t nsel = rows ? n_rows : w->out_features;
     const float c = step_coeff(alpha, N, sigma);
@@ -553,8 +563,8 @@ int oracle_update(oracle_tensor *w, const uint64_t *seeds_t, const float *fit_t,
             const uint64_t pair = (uint64_t)(n * K + k) >> 1;
             const int32_t wq[2] = { load_q(w, n, k), load_q(w, n, k + 1) };
             float res[2], g[2];
-            replay_pair(w, hist_seeds, hist_fit, hist_len, N, sigma, c, gamma, pair, wq, res);
-            aggregate_pair(seeds_t, fit_t, N, w->tensor_id, pair, sigma, g);
+            replay_pair(w, hist_seeds, hist_fit, hist_len, N, sigma, c, gamma, pair, wq, antithetic, res);
+            aggregate_pair(seeds_t, fit_t, N, w->tensor_id, pair, sigma, antithetic, g);
             for (int l = 0; l < 2; ++l) {
                 float u;
                 int32_t raw;
@@ -587,7 +597,7 @@ int oracle_update_full_residual(oracle_tensor *w, const uint64_t *seeds_t, const
         for (int64_t k = 0; k < K; k += 2) {
             const uint64_t e0 = (uint64_t)((int64_t)n * K + k);
             float g[2];
-            aggregate_pair(seeds_t, fit_t, N, w->tensor_id, e0 >> 1, sigma, g);
+            aggregate_pair(seeds_t, fit_t, N, w->tensor_id, e0 >> 1, sigma, 0, g);
             for (int l = 0; l < 2; ++l) {
                 int32_t wq = load_q(w, n, k + l);
                 float u;
@@ -606,15 +616,16 @@ int oracle_update_full_residual(oracle_tensor *w, const uint64_t *seeds_t, const
 
 /* g = Σ_i F_i δ_i per element (Eq. 5 without the 1/(Nσ) factor), for pins */
 int oracle_aggregate(const oracle_tensor *w, const uint64_t *seeds, const float *fit, int32_t N,
-                     float sigma, float *g_out)
+                     float sigma, float *g_out, int32_t antithetic)
 {
     if (!tensor_ok(w) || !seeds || !fit || !g_out || N <= 0) return ORACLE_ERR_INVALID_ARG;
+    if (antithetic && (N & 1)) return ORACLE_ERR_INVALID_ARG;
     const int64_t K = w->in_features;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int32_t n = 0; n < w->out_features; ++n)
         for (int64_t k = 0; k < K; k += 2) {
             float g[2];
-            aggregate_pair(seeds, fit, N, w->tensor_id, (uint64_t)((int64_t)n * K + k) >> 1, sigma, g);
+            aggregate_pair(seeds, fit, N, w->tensor_id, (uint64_t)((int64_t)n * K + k) >> 1, sigma, antithetic, g);
             g_out[(int64_t)n * K + k] = g[0];
             g_out[(int64_t)n * K + k + 1] = g[1];
         }

@@ -56,9 +56,12 @@ def _load():
         "qes_noise_delta": ([u64, u32, u64, u64, f32, vp, vp], i32),
         "qes_noise_from_words": ([vp, u64, f32, vp, vp, vp], i32),
         "qes_perturbed_qgemm": ([tp, vp, vp, i32, f32, vp, i32, vp, i32, vp, sz, vp], i32),
+        "qes_perturbed_qgemm_antithetic": ([tp, vp, vp, i32, f32, vp, i32, vp, i32, vp, sz, vp], i32),
         "qes_gemm_workspace_bytes": ([tp, i32, i32, i32], sz),
         "qes_update": ([tp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
         "qes_replay_residual": ([tp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
+        "qes_update_antithetic": ([tp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
+        "qes_replay_residual_antithetic": ([tp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
         "qes_normalize_fitness": ([vp, i32, vp], i32),
         "qes_bench_noise": ([i32, u64, i32, f32, vp, vp], i32),
         "qes_bench_copy": ([vp, vp, sz, vp], i32),
@@ -75,7 +78,8 @@ def _load():
 
 
 EXPORTS = ["qes_noise_words", "qes_noise_gauss", "qes_noise_delta", "qes_noise_from_words", "qes_perturbed_qgemm",
-           "qes_gemm_workspace_bytes", "qes_update", "qes_replay_residual", "qes_normalize_fitness",
+           "qes_perturbed_qgemm_antithetic", "qes_gemm_workspace_bytes", "qes_update", "qes_update_antithetic",
+           "qes_replay_residual", "qes_replay_residual_antithetic", "qes_normalize_fitness",
            "qes_bench_noise", "qes_bench_copy", "qes_status_string", "qes_last_hip_error",
            "qes_abi_version"]
 
@@ -166,51 +170,57 @@ def gemm_workspace_bytes(w, N, T, act_mode):
     return int(_load().qes_gemm_workspace_bytes(ctypes.byref(d), N, T, act_mode))
 
 
-def perturbed_qgemm(w, seeds, sigma, x, y, act_mode=0, perturb_mask=None, workspace=None, stream=None):
-    """x: device bf16 [N,T,in]; y: device bf16 [N,T,out] (written). seeds: host uint64 [N]."""
+def perturbed_qgemm(w, seeds, sigma, x, y, act_mode=0, perturb_mask=None, workspace=None, stream=None,
+                    antithetic=False):
+    """x: device bf16 [N,T,in]; y: device bf16 [N,T,out] (written). seeds: host uint64 [N], or [N/2]
+    pair seeds with antithetic=True (qes_perturbed_qgemm_antithetic)."""
     seeds = _host(seeds, np.uint64)
     mask = _host(perturb_mask, np.uint8)
     N, T = int(x.shape[0]), int(x.shape[1])
-    if seeds.size != N or (mask is not None and mask.size != N):
-        raise ValueError("seeds / perturb_mask must have one entry per member")
+    if seeds.size != (N // 2 if antithetic else N) or (mask is not None and mask.size != N) or (antithetic and N % 2):
+        raise ValueError("seeds / perturb_mask do not match the population")
     if x.shape[2] != w.in_features or tuple(y.shape) != (N, T, w.out_features):
         raise ValueError("x / y shapes do not match the tensor")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     d = w.desc()
-    _check(_load().qes_perturbed_qgemm(ctypes.byref(d), _hptr(seeds), _hptr(mask), N, sigma, _dev_ptr(x, "x"), T,
-                                       _dev_ptr(y, "y"), act_mode, _dev_ptr(workspace, "workspace"), ws_bytes,
-                                       _stream(stream)), "qes_perturbed_qgemm")
+    fn = _load().qes_perturbed_qgemm_antithetic if antithetic else _load().qes_perturbed_qgemm
+    _check(fn(ctypes.byref(d), _hptr(seeds), _hptr(mask), N, sigma, _dev_ptr(x, "x"), T, _dev_ptr(y, "y"), act_mode,
+              _dev_ptr(workspace, "workspace"), ws_bytes, _stream(stream)),
+           "qes_perturbed_qgemm_antithetic" if antithetic else "qes_perturbed_qgemm")
 
 
-def _hist(hist_seeds, hist_fit, N):
+def _hist(hist_seeds, hist_fit, N, antithetic=False):
     if hist_seeds is None or len(hist_seeds) == 0:
         return None, None, 0
-    hs = _host(hist_seeds, np.uint64).reshape(-1, N)
+    hs = _host(hist_seeds, np.uint64).reshape(-1, N // 2 if antithetic else N)
     hf = _host(hist_fit, np.float32).reshape(-1, N)
-    if hs.shape != hf.shape:
-        raise ValueError("history seeds and fitnesses differ in shape")
+    if hs.shape[0] != hf.shape[0]:
+        raise ValueError("history seeds and fitnesses differ in length")
     return hs, hf, int(hs.shape[0])
 
 
-def update(w, seeds_t, fit_t, hist_seeds, hist_fit, sigma, alpha, gamma, stats=None, stream=None):
-    """In-place Alg. 2 on w.qweight. stats: device int64/uint64 tensor [2] or None."""
+def update(w, seeds_t, fit_t, hist_seeds, hist_fit, sigma, alpha, gamma, stats=None, stream=None, antithetic=False):
+    """In-place Alg. 2 on w.qweight. stats: device int64/uint64 tensor [2] or None. antithetic=True:
+    one seed per pair (N/2 per generation), one fitness per member (qes_update_antithetic)."""
     seeds_t = _host(seeds_t, np.uint64)
     fit_t = _host(fit_t, np.float32)
-    N = int(seeds_t.size)
-    if fit_t.size != N:
-        raise ValueError("seeds_t and fit_t differ in length")
-    hs, hf, hl = _hist(hist_seeds, hist_fit, N)
+    N = int(fit_t.size)
+    if seeds_t.size != (N // 2 if antithetic else N) or (antithetic and N % 2):
+        raise ValueError("seeds_t and fit_t do not match")
+    hs, hf, hl = _hist(hist_seeds, hist_fit, N, antithetic)
     d = w.desc()
-    _check(_load().qes_update(ctypes.byref(d), _hptr(seeds_t), _hptr(fit_t), _hptr(hs), _hptr(hf), hl, N, sigma,
-                              alpha, gamma, _dev_ptr(stats, "stats"), _stream(stream)), "qes_update")
+    fn = _load().qes_update_antithetic if antithetic else _load().qes_update
+    _check(fn(ctypes.byref(d), _hptr(seeds_t), _hptr(fit_t), _hptr(hs), _hptr(hf), hl, N, sigma, alpha, gamma,
+              _dev_ptr(stats, "stats"), _stream(stream)), "qes_update_antithetic" if antithetic else "qes_update")
 
 
-def replay_residual(w, hist_seeds, hist_fit, N, sigma, alpha, gamma, residual, stream=None):
+def replay_residual(w, hist_seeds, hist_fit, N, sigma, alpha, gamma, residual, stream=None, antithetic=False):
     """residual: device float32 [out,in] (written)."""
-    hs, hf, hl = _hist(hist_seeds, hist_fit, N)
+    hs, hf, hl = _hist(hist_seeds, hist_fit, N, antithetic)
     d = w.desc()
-    _check(_load().qes_replay_residual(ctypes.byref(d), _hptr(hs), _hptr(hf), hl, N, sigma, alpha, gamma,
-                                       _dev_ptr(residual, "residual"), _stream(stream)), "qes_replay_residual")
+    fn = _load().qes_replay_residual_antithetic if antithetic else _load().qes_replay_residual
+    _check(fn(ctypes.byref(d), _hptr(hs), _hptr(hf), hl, N, sigma, alpha, gamma, _dev_ptr(residual, "residual"),
+              _stream(stream)), "qes_replay_residual_antithetic" if antithetic else "qes_replay_residual")
 
 
 def normalize_fitness(reward):

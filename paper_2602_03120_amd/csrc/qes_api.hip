@@ -90,31 +90,39 @@ int tensor_check(const qes_tensor *w)
 }
 
 // Validates the update/replay scalars and fills the entry array (history first, current last).
-// Also bounds |u| so that the float -> int conversion in the kernel can never overflow.
-int fill_entries(qes::Entry *dst, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
-                 const float *hist_fit, int32_t hist_len, int32_t N, double c)
+// One record per member, or per antithetic pair (then `stride` = 2 fitnesses per record: the +δ
+// member's in fit_bits, the -δ member's in pad). Also bounds |u| so that the float -> int
+// conversion in the kernel can never overflow.
+int fill_generation(qes::Entry *dst, const uint64_t *seeds, const float *fit, int32_t records, int stride,
+                    double *abs_sum)
 {
+    for (int32_t i = 0; i < records; ++i) {
+        uint32_t fb[2] = {0u, 0u};
+        for (int k = 0; k < stride; ++k) {
+            const float f = fit[(size_t)i * stride + k];
+            if (!std::isfinite(f)) return QES_ERR_INVALID_ARG;
+            *abs_sum += std::fabs((double)f);
+            std::memcpy(&fb[k], &f, 4);
+        }
+        dst[i] = qes::Entry{(uint32_t)seeds[i], (uint32_t)(seeds[i] >> 32), fb[0], fb[1]};
+    }
+    return QES_OK;
+}
+
+int fill_entries(qes::Entry *dst, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
+                 const float *hist_fit, int32_t hist_len, int32_t N, bool antithetic, double c)
+{
+    const int stride = antithetic ? 2 : 1;
+    const int32_t records = N / stride;
     double abs_sum = 0.0;
-    size_t o = 0;
-    for (int32_t tau = 0; tau < hist_len; ++tau)
-        for (int32_t i = 0; i < N; ++i, ++o) {
-            const float f = hist_fit[(size_t)tau * N + i];
-            if (!std::isfinite(f)) return QES_ERR_INVALID_ARG;
-            abs_sum += std::fabs((double)f);
-            const uint64_t s = hist_seeds[(size_t)tau * N + i];
-            uint32_t fb;
-            std::memcpy(&fb, &f, 4);
-            dst[o] = qes::Entry{(uint32_t)s, (uint32_t)(s >> 32), fb, 0u};
-        }
+    for (int32_t tau = 0; tau < hist_len; ++tau) {
+        const int rc = fill_generation(dst + (size_t)tau * records, hist_seeds + (size_t)tau * records,
+                                       hist_fit + (size_t)tau * N, records, stride, &abs_sum);
+        if (rc != QES_OK) return rc;
+    }
     if (seeds_t) {
-        for (int32_t i = 0; i < N; ++i, ++o) {
-            const float f = fit_t[i];
-            if (!std::isfinite(f)) return QES_ERR_INVALID_ARG;
-            abs_sum += std::fabs((double)f);
-            uint32_t fb;
-            std::memcpy(&fb, &f, 4);
-            dst[o] = qes::Entry{(uint32_t)seeds_t[i], (uint32_t)(seeds_t[i] >> 32), fb, 0u};
-        }
+        const int rc = fill_generation(dst + (size_t)hist_len * records, seeds_t, fit_t, records, stride, &abs_sum);
+        if (rc != QES_OK) return rc;
     }
     // |δ| <= 8 and 0 <= γ <= 1, so |u| <= |c|·8·Σ|F| over every generation replayed
     if (std::fabs(c) * 8.0 * abs_sum >= 1073741824.0) return QES_ERR_INVALID_ARG;
@@ -123,11 +131,12 @@ int fill_entries(qes::Entry *dst, const uint64_t *seeds_t, const float *fit_t, c
 
 int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
                   const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
-                  uint64_t *stats, float *residual, bool replay_only, void *stream)
+                  uint64_t *stats, float *residual, bool replay_only, bool antithetic, void *stream)
 {
     int rc = tensor_check(w);
     if (rc != QES_OK) return rc;
     if (N <= 0 || N > QES_MAX_POPULATION || hist_len < 0 || hist_len > QES_MAX_HISTORY) return QES_ERR_INVALID_ARG;
+    if (antithetic && (N & 1)) return QES_ERR_INVALID_ARG;
     if (hist_len > 0 && (!hist_seeds || !hist_fit)) return QES_ERR_INVALID_ARG;
     if (!replay_only && (!seeds_t || !fit_t)) return QES_ERR_INVALID_ARG;
     if (replay_only && (!residual || ((uintptr_t)residual & 15u) != 0)) return QES_ERR_INVALID_ARG;
@@ -137,7 +146,8 @@ int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit
 
     const double c64 = (double)alpha / ((double)N * (double)sigma);
     const int32_t steps = hist_len + (replay_only ? 0 : 1);
-    const size_t n_entries = (size_t)steps * (size_t)N;
+    const int32_t records = antithetic ? N / 2 : N;   // one record per member, or per antithetic pair
+    const size_t n_entries = (size_t)steps * (size_t)records;
     hipStream_t s = (hipStream_t)stream;
 
     qes::UpdateArgs a{};
@@ -147,7 +157,7 @@ int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit
     a.stats = (unsigned long long *)stats;
     a.n_pairs = (uint32_t)(((uint64_t)w->out_features * (uint64_t)w->in_features) >> 1);
     a.steps = steps;
-    a.N = N;
+    a.N = records;
     a.sigma = sigma;
     a.c = (float)c64;
     a.gamma = gamma;
@@ -161,12 +171,12 @@ int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit
         rc = acquire_slot(n_entries * sizeof(qes::Entry), &slot);
         if (rc != QES_OK) return rc;
         rc = fill_entries((qes::Entry *)slot->host, replay_only ? nullptr : seeds_t, fit_t, hist_seeds, hist_fit,
-                          hist_len, N, c64);
+                          hist_len, N, antithetic, c64);
         if (rc != QES_OK) return rc;
         QES_HIP(hipMemcpyAsync(slot->dev, slot->host, n_entries * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
         a.entries = (const qes::Entry *)slot->dev;
     }
-    hipError_t e = qes::launch_update(a, w->bits, replay_only, s);
+    hipError_t e = qes::launch_update(a, w->bits, replay_only, antithetic, s);
     if (slot) {
         // the slot is busy until everything enqueued so far (copy and kernel) has run
         hipError_t e2 = hipEventRecord(slot->ev, s);
@@ -244,12 +254,13 @@ size_t qes_gemm_workspace_bytes(const qes_tensor *w, int32_t N, int32_t T, int32
     return xq + rows * sizeof(float);
 }
 
-int qes_perturbed_qgemm(const qes_tensor *w, const uint64_t *seeds, const uint8_t *perturb_mask, int32_t N,
-                        float sigma, const void *x, int32_t T, void *y, int32_t act_mode, void *workspace,
-                        size_t workspace_bytes, void *stream)
+static int gemm_common(const qes_tensor *w, const uint64_t *seeds, const uint8_t *perturb_mask, int32_t N,
+                       float sigma, const void *x, int32_t T, void *y, int32_t act_mode, void *workspace,
+                       size_t workspace_bytes, bool antithetic, void *stream)
 {
     int rc = tensor_check(w);
     if (rc != QES_OK) return rc;
+    if (antithetic && (N & 1)) return QES_ERR_INVALID_ARG;
     if (!w->scales || !seeds || !x || !y || N <= 0 || N > QES_MAX_POPULATION || T <= 0) return QES_ERR_INVALID_ARG;
     if (((uintptr_t)x & 15u) != 0 || ((uintptr_t)y & 1u) != 0 || ((uintptr_t)w->scales & 1u) != 0)
         return QES_ERR_INVALID_ARG;
@@ -294,9 +305,12 @@ int qes_perturbed_qgemm(const qes_tensor *w, const uint64_t *seeds, const uint8_
     rc = acquire_slot((size_t)N * sizeof(qes::Entry), &slot);
     if (rc != QES_OK) return rc;
     qes::Entry *ent = (qes::Entry *)slot->host;
-    for (int32_t i = 0; i < N; ++i)
-        ent[i] = qes::Entry{(uint32_t)seeds[i], (uint32_t)(seeds[i] >> 32),
-                            (perturb_mask == nullptr || perturb_mask[i] != 0) ? 1u : 0u, 0u};
+    for (int32_t i = 0; i < N; ++i) {
+        // antithetic pairs: members 2j and 2j+1 share seed j; the odd member uses -δ (mode 2)
+        const uint64_t sd = antithetic ? seeds[i / 2] : seeds[i];
+        const uint32_t mode = (perturb_mask != nullptr && perturb_mask[i] == 0) ? 0u : ((antithetic && (i & 1)) ? 2u : 1u);
+        ent[i] = qes::Entry{(uint32_t)sd, (uint32_t)(sd >> 32), mode, 0u};
+    }
     QES_HIP(hipMemcpyAsync(slot->dev, slot->host, (size_t)N * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
     a.entries = (const qes::Entry *)slot->dev;
     hipError_t e = qes::launch_gemm(a, w->bits, act_mode, s);
@@ -307,19 +321,50 @@ int qes_perturbed_qgemm(const qes_tensor *w, const uint64_t *seeds, const uint8_
     return QES_OK;
 }
 
+int qes_perturbed_qgemm(const qes_tensor *w, const uint64_t *seeds, const uint8_t *perturb_mask, int32_t N,
+                        float sigma, const void *x, int32_t T, void *y, int32_t act_mode, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    return gemm_common(w, seeds, perturb_mask, N, sigma, x, T, y, act_mode, workspace, workspace_bytes, false, stream);
+}
+
+int qes_perturbed_qgemm_antithetic(const qes_tensor *w, const uint64_t *pair_seeds, const uint8_t *perturb_mask,
+                                   int32_t N, float sigma, const void *x, int32_t T, void *y, int32_t act_mode,
+                                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gemm_common(w, pair_seeds, perturb_mask, N, sigma, x, T, y, act_mode, workspace, workspace_bytes, true,
+                       stream);
+}
+
 int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
                const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
                uint64_t *stats, void *stream)
 {
     return update_common(w, seeds_t, fit_t, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, stats, nullptr,
-                         false, stream);
+                         false, false, stream);
+}
+
+int qes_update_antithetic(qes_tensor *w, const uint64_t *pair_seeds_t, const float *fit_t,
+                          const uint64_t *hist_pair_seeds, const float *hist_fit, int32_t hist_len, int32_t N,
+                          float sigma, float alpha, float gamma, uint64_t *stats, void *stream)
+{
+    return update_common(w, pair_seeds_t, fit_t, hist_pair_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, stats,
+                         nullptr, false, true, stream);
 }
 
 int qes_replay_residual(const qes_tensor *w, const uint64_t *hist_seeds, const float *hist_fit, int32_t hist_len,
                         int32_t N, float sigma, float alpha, float gamma, float *residual, void *stream)
 {
     return update_common(w, nullptr, nullptr, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, nullptr,
-                         residual, true, stream);
+                         residual, true, false, stream);
+}
+
+int qes_replay_residual_antithetic(const qes_tensor *w, const uint64_t *hist_pair_seeds, const float *hist_fit,
+                                   int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
+                                   float *residual, void *stream)
+{
+    return update_common(w, nullptr, nullptr, hist_pair_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, nullptr,
+                         residual, true, true, stream);
 }
 
 int qes_normalize_fitness(const float *reward, int32_t N, float *fit)

@@ -93,14 +93,15 @@ __device__ __forceinline__ bool block_to_work(uint32_t n_tiles, uint32_t n_membe
     return true;
 }
 
-// One pair: draw, gate (Eq. 4) in place.
+// One pair: draw, gate (Eq. 4) in place. SIGN = -1 is the mirrored member of an antithetic pair.
+template <int SIGN>
 __device__ __forceinline__ void perturb_pair(int32_t &w0, int32_t &w1, uint32_t k0, uint32_t k1, uint32_t tensor_id,
                                              uint32_t pair, float sigma, int32_t qmin, uint32_t qspan)
 {
     int32_t d0, d1;
     delta_pair(k0, k1, tensor_id, pair, sigma, d0, d1);
-    w0 = gate(w0, d0, qmin, qspan);
-    w1 = gate(w1, d1, qmin, qspan);
+    w0 = gate(w0, SIGN < 0 ? -d0 : d0, qmin, qspan);
+    w1 = gate(w1, SIGN < 0 ? -d1 : d1, qmin, qspan);
 }
 
 // exact bf16 images of two small integers in one dword (low half = first element)
@@ -205,7 +206,7 @@ struct Gemm {
     }
 
     // this wave's half of a B fragment of substep s: draw, gate (Eq. 4), pack as exact small integers
-    template <bool PERTURB>
+    template <int PERTURB>
     __device__ __forceinline__ uint2 make_half(int s, uint2 raw, bool zero) const
     {
         int32_t w[H];
@@ -222,11 +223,11 @@ struct Gemm {
                 w[4 + j] = ((int32_t)(raw.y << (24 - 8 * j))) >> 24;
             }
         }
-        if (PERTURB) {
+        if (PERTURB != 0) {
             const uint32_t pair = pair0 + (uint32_t)s * (kSubK / 2);
 #pragma unroll
             for (int p = 0; p < H / 2; ++p)
-                perturb_pair(w[2 * p], w[2 * p + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair + p, a.sigma, a.qmin,
+                perturb_pair<PERTURB>(w[2 * p], w[2 * p + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair + p, a.sigma, a.qmin,
                              a.qspan);
         }
         uint2 d;
@@ -249,7 +250,7 @@ struct Gemm {
     // ---- one substep: MFMAs of the fragments of substep s on tile buffer `xbuf`, this wave's half
     // fragment of substep s+1 underneath. PAR is the parity of s: it selects the B-fragment buffer
     // at compile time.
-    template <bool PERTURB, int PAR>
+    template <int PERTURB, int PAR>
     __device__ __forceinline__ void substep(int s, const char *xbuf, char *xbuf_next)
     {
         const bool has_next = (s + 1) < n_sub;
@@ -322,7 +323,7 @@ struct Gemm {
         __syncthreads();
     }
 
-    template <bool PERTURB>
+    template <int PERTURB>
     __device__ __forceinline__ void pass(int t0, int n0, char *x0, char *x1, uint16_t *yg, const float *xs,
                                          const float (&s_row)[kWR])
     {
@@ -431,11 +432,12 @@ __global__ __launch_bounds__(kThreads, (TM >= 512 ? 4 : 1)) void gemm_kernel(con
     g.bfrag = bfrag;
     uint16_t *yg = (uint16_t *)a.y + (size_t)member * a.T * a.out_features;
     const float *xs = G::kI8 ? a.x_scale + (size_t)member * a.T : nullptr;
-    const bool perturb = (g.en.fit_bits != 0u) && (a.sigma != 0.0f);
+    const uint32_t mode = (a.sigma != 0.0f) ? g.en.fit_bits : 0u;   // 0 base weights, 1 +δ, 2 -δ (antithetic mirror)
 
     for (int t0 = 0; t0 < a.T; t0 += TM) {
-        if (perturb) g.template pass<true>(t0, n0, x0, x1, yg, xs, s_row);
-        else g.template pass<false>(t0, n0, x0, x1, yg, xs, s_row);
+        if (mode == 1u) g.template pass<1>(t0, n0, x0, x1, yg, xs, s_row);
+        else if (mode == 2u) g.template pass<-1>(t0, n0, x0, x1, yg, xs, s_row);
+        else g.template pass<0>(t0, n0, x0, x1, yg, xs, s_row);
     }
 }
 

@@ -9,8 +9,8 @@ namespace qes {
 // One (seed, fitness) record as the kernels read it: 16 bytes, one scalar load.
 struct Entry {
     uint32_t seed_lo, seed_hi;
-    uint32_t fit_bits;   // float bits (update/replay) or perturb flag (GEMM)
-    uint32_t pad;
+    uint32_t fit_bits;   // update/replay: fitness bits. GEMM: 0 = base weights, 1 = +δ, 2 = -δ
+    uint32_t pad;        // update/replay with antithetic pairs: fitness bits of the -δ member
 };
 
 struct UpdateArgs {
@@ -20,7 +20,7 @@ struct UpdateArgs {
     unsigned long long *stats;   // update only, may be null
     uint32_t n_pairs;            // out*in/2
     int32_t steps;               // generations to run (hist_len for replay, hist_len+1 for update)
-    int32_t N;
+    int32_t N;                   // records per generation (members, or pairs when antithetic)
     float sigma, c, gamma;
     int32_t qmin;
     uint32_t qspan;              // qmax - qmin
@@ -55,7 +55,7 @@ hipError_t launch_bench_noise(int mode, uint64_t n_threads, int iters, float sig
 hipError_t launch_bench_copy(const void *src, void *dst, size_t n_bytes, hipStream_t s);
 
 // bits: 4|8; residual: write fp32 residual instead of updating the weights
-hipError_t launch_update(const UpdateArgs &a, int bits, bool residual, hipStream_t s);
+hipError_t launch_update(const UpdateArgs &a, int bits, bool residual, bool antithetic, hipStream_t s);
 
 hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_scale, int64_t rows,
                                        int32_t in_features, hipStream_t s);

@@ -93,7 +93,7 @@ struct Raw {
     }
 };
 
-template <int BITS, int PPT, bool RESIDUAL, bool CLAMP>
+template <int BITS, int PPT, bool RESIDUAL, bool CLAMP, bool ANTI>
 __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
 {
     using P = Pack<BITS>;
@@ -121,12 +121,17 @@ __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
         for (int32_t i = 0; i < a.N; ++i) {
             const Entry en = ent[tau * a.N + i];          // wave-uniform: scalar load
             const float fit = __uint_as_float(en.fit_bits);
+            const float fit_mirror = __uint_as_float(en.pad);   // antithetic pairs: fitness of the -δ member
 #pragma unroll
             for (int j = 0; j < PPT; ++j) {
                 float d0, d1;
                 delta_pair_f32<CLAMP>(en.seed_lo, en.seed_hi, a.tensor_id, pair0 + j, a.sigma, d0, d1);
                 g[2 * j] = __builtin_fmaf(fit, d0, g[2 * j]);
                 g[2 * j + 1] = __builtin_fmaf(fit, d1, g[2 * j + 1]);
+                if (ANTI) {   // one draw serves members 2i (+δ) and 2i+1 (-δ), summed in member order
+                    g[2 * j] = __builtin_fmaf(fit_mirror, -d0, g[2 * j]);
+                    g[2 * j + 1] = __builtin_fmaf(fit_mirror, -d1, g[2 * j + 1]);
+                }
             }
         }
         const bool last = !RESIDUAL && (tau == a.steps - 1);
@@ -170,8 +175,18 @@ __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
     }
 }
 
+template <int BITS, bool RESIDUAL, bool CLAMP, bool ANTI>
+void launch_ppt(const UpdateArgs &a, int ppt, unsigned blocks, hipStream_t s)
+{
+    switch (ppt) {
+    case 4: update_kernel<BITS, 4, RESIDUAL, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
+    case 2: update_kernel<BITS, 2, RESIDUAL, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
+    default: update_kernel<BITS, 1, RESIDUAL, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
+    }
+}
+
 template <int BITS, bool RESIDUAL>
-hipError_t launch_ppt(const UpdateArgs &a, hipStream_t s)
+hipError_t launch_variant(const UpdateArgs &a, bool antithetic, hipStream_t s)
 {
     // Enough threads to fill 256 CUs x 4 SIMDs several waves deep, else fewer pairs per thread.
     const uint64_t want_threads = 256ull * 4 * 64 * 4;
@@ -182,28 +197,23 @@ hipError_t launch_ppt(const UpdateArgs &a, hipStream_t s)
     // |sigma*eps| <= 1.2 * 5.77 < 7: the 4-bit container clamp cannot fire and is compiled out
     const bool clamp = !(a.sigma <= 1.2f);
     if (clamp) {
-        switch (ppt) {
-        case 4: update_kernel<BITS, 4, RESIDUAL, true><<<blocks, kBlock, 0, s>>>(a); break;
-        case 2: update_kernel<BITS, 2, RESIDUAL, true><<<blocks, kBlock, 0, s>>>(a); break;
-        default: update_kernel<BITS, 1, RESIDUAL, true><<<blocks, kBlock, 0, s>>>(a); break;
-        }
+        if (antithetic) launch_ppt<BITS, RESIDUAL, true, true>(a, ppt, blocks, s);
+        else launch_ppt<BITS, RESIDUAL, true, false>(a, ppt, blocks, s);
     } else {
-        switch (ppt) {
-        case 4: update_kernel<BITS, 4, RESIDUAL, false><<<blocks, kBlock, 0, s>>>(a); break;
-        case 2: update_kernel<BITS, 2, RESIDUAL, false><<<blocks, kBlock, 0, s>>>(a); break;
-        default: update_kernel<BITS, 1, RESIDUAL, false><<<blocks, kBlock, 0, s>>>(a); break;
-        }
+        if (antithetic) launch_ppt<BITS, RESIDUAL, false, true>(a, ppt, blocks, s);
+        else launch_ppt<BITS, RESIDUAL, false, false>(a, ppt, blocks, s);
     }
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_update(const UpdateArgs &a, int bits, bool residual, hipStream_t s)
+hipError_t launch_update(const UpdateArgs &a, int bits, bool residual, bool antithetic, hipStream_t s)
 {
     if (a.n_pairs == 0) return hipSuccess;
-    if (bits == 4) return residual ? launch_ppt<4, true>(a, s) : launch_ppt<4, false>(a, s);
-    return residual ? launch_ppt<8, true>(a, s) : launch_ppt<8, false>(a, s);
+    if (bits == 4)
+        return residual ? launch_variant<4, true>(a, antithetic, s) : launch_variant<4, false>(a, antithetic, s);
+    return residual ? launch_variant<8, true>(a, antithetic, s) : launch_variant<8, false>(a, antithetic, s);
 }
 
 }  // namespace qes
