@@ -192,6 +192,16 @@ int qes_replay_residual_antithetic(const qes_tensor *w, const uint64_t *hist_pai
                                    float *residual, void *stream);
 
 /*
+ * Alg. 1, the Full-Residual variant (§3.2 Eq. 6-8 with an explicitly stored residual): one step
+ *   g = Σ_i fit_t[i]·δ(seeds_t[i]);  u = c·g + γ·e;  Δ = Round(u);  Δf = Δ if in range else 0;
+ *   W ← W + Δf;  e ← u − Δf
+ * e_state: DEVICE float32 [out_features, in_features], 16-byte aligned, read and written; the
+ * caller zeroes it before the first step. Other arguments as for qes_update (no history).
+ */
+int qes_update_full_residual(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, int32_t N, float sigma,
+                             float alpha, float gamma, float *e_state, uint64_t *stats, void *stream);
+
+/*
  * Alg. 1 "normalize reward for population": z-score with the population standard deviation,
  * computed in fp64; zero variance or N < 2 gives all zeros. HOST in, HOST out, no GPU work.
  */

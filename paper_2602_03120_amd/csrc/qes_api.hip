@@ -131,15 +131,17 @@ int fill_entries(qes::Entry *dst, const uint64_t *seeds_t, const float *fit_t, c
 
 int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
                   const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
-                  uint64_t *stats, float *residual, bool replay_only, bool antithetic, void *stream)
+                  uint64_t *stats, float *residual, int rmode, bool antithetic, void *stream)
 {
     int rc = tensor_check(w);
     if (rc != QES_OK) return rc;
     if (N <= 0 || N > QES_MAX_POPULATION || hist_len < 0 || hist_len > QES_MAX_HISTORY) return QES_ERR_INVALID_ARG;
     if (antithetic && (N & 1)) return QES_ERR_INVALID_ARG;
+    const bool replay_only = (rmode == 1);
+    if (rmode == 2 && hist_len != 0) return QES_ERR_INVALID_ARG;
     if (hist_len > 0 && (!hist_seeds || !hist_fit)) return QES_ERR_INVALID_ARG;
     if (!replay_only && (!seeds_t || !fit_t)) return QES_ERR_INVALID_ARG;
-    if (replay_only && (!residual || ((uintptr_t)residual & 15u) != 0)) return QES_ERR_INVALID_ARG;
+    if (rmode != 0 && (!residual || ((uintptr_t)residual & 15u) != 0)) return QES_ERR_INVALID_ARG;
     if (!(sigma > 0.0f) || !std::isfinite(sigma) || !std::isfinite(alpha)) return QES_ERR_INVALID_ARG;
     if (!(gamma >= 0.0f && gamma <= 1.0f)) return QES_ERR_INVALID_ARG;
     if (stats && ((uintptr_t)stats & 7u) != 0) return QES_ERR_INVALID_ARG;
@@ -176,7 +178,7 @@ int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit
         QES_HIP(hipMemcpyAsync(slot->dev, slot->host, n_entries * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
         a.entries = (const qes::Entry *)slot->dev;
     }
-    hipError_t e = qes::launch_update(a, w->bits, replay_only, antithetic, s);
+    hipError_t e = qes::launch_update(a, w->bits, rmode, antithetic, s);
     if (slot) {
         // the slot is busy until everything enqueued so far (copy and kernel) has run
         hipError_t e2 = hipEventRecord(slot->ev, s);
@@ -341,7 +343,7 @@ int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const
                uint64_t *stats, void *stream)
 {
     return update_common(w, seeds_t, fit_t, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, stats, nullptr,
-                         false, false, stream);
+                         0, false, stream);
 }
 
 int qes_update_antithetic(qes_tensor *w, const uint64_t *pair_seeds_t, const float *fit_t,
@@ -349,14 +351,14 @@ int qes_update_antithetic(qes_tensor *w, const uint64_t *pair_seeds_t, const flo
                           float sigma, float alpha, float gamma, uint64_t *stats, void *stream)
 {
     return update_common(w, pair_seeds_t, fit_t, hist_pair_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, stats,
-                         nullptr, false, true, stream);
+                         nullptr, 0, true, stream);
 }
 
 int qes_replay_residual(const qes_tensor *w, const uint64_t *hist_seeds, const float *hist_fit, int32_t hist_len,
                         int32_t N, float sigma, float alpha, float gamma, float *residual, void *stream)
 {
     return update_common(w, nullptr, nullptr, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, nullptr,
-                         residual, true, false, stream);
+                         residual, 1, false, stream);
 }
 
 int qes_replay_residual_antithetic(const qes_tensor *w, const uint64_t *hist_pair_seeds, const float *hist_fit,
@@ -364,7 +366,14 @@ int qes_replay_residual_antithetic(const qes_tensor *w, const uint64_t *hist_pai
                                    float *residual, void *stream)
 {
     return update_common(w, nullptr, nullptr, hist_pair_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, nullptr,
-                         residual, true, true, stream);
+                         residual, 1, true, stream);
+}
+
+int qes_update_full_residual(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, int32_t N, float sigma,
+                             float alpha, float gamma, float *e_state, uint64_t *stats, void *stream)
+{
+    return update_common(w, seeds_t, fit_t, nullptr, nullptr, 0, N, sigma, alpha, gamma, stats, e_state, 2, false,
+                         stream);
 }
 
 int qes_normalize_fitness(const float *reward, int32_t N, float *fit)

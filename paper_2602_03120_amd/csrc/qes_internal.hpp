@@ -16,7 +16,7 @@ struct Entry {
 struct UpdateArgs {
     void *qweight;
     const Entry *entries;        // [steps][N], oldest generation first, current step last
-    float *residual;             // replay only
+    float *residual;             // replay: written; full-residual step: read and written
     unsigned long long *stats;   // update only, may be null
     uint32_t n_pairs;            // out*in/2
     int32_t steps;               // generations to run (hist_len for replay, hist_len+1 for update)
@@ -54,8 +54,8 @@ hipError_t launch_bench_noise(int mode, uint64_t n_threads, int iters, float sig
                               hipStream_t s);
 hipError_t launch_bench_copy(const void *src, void *dst, size_t n_bytes, hipStream_t s);
 
-// bits: 4|8; residual: write fp32 residual instead of updating the weights
-hipError_t launch_update(const UpdateArgs &a, int bits, bool residual, bool antithetic, hipStream_t s);
+// bits: 4|8; rmode 0: Alg. 2 in place; 1: replay only, residual written; 2: Alg. 1 step on a stored residual
+hipError_t launch_update(const UpdateArgs &a, int bits, int rmode, bool antithetic, hipStream_t s);
 
 hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_scale, int64_t rows,
                                        int32_t in_features, hipStream_t s);

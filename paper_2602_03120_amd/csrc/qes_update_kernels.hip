@@ -93,7 +93,9 @@ struct Raw {
     }
 };
 
-template <int BITS, int PPT, bool RESIDUAL, bool CLAMP, bool ANTI>
+// RMODE 0: Alg. 2 (replay + update in place). 1: replay only, residual written. 2: Alg. 1 step with a
+// stored residual (read, advanced one generation, written back together with the weights).
+template <int BITS, int PPT, int RMODE, bool CLAMP, bool ANTI>
 __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
 {
     using P = Pack<BITS>;
@@ -110,7 +112,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
 
     float res[2 * PPT];
 #pragma unroll
-    for (int j = 0; j < 2 * PPT; ++j) res[j] = 0.0f;
+    for (int j = 0; j < 2 * PPT; ++j) res[j] = (RMODE == 2) ? a.residual[(size_t)pair0 * 2 + j] : 0.0f;
 
     uint32_t changed = 0, gated = 0;
     const Entry *__restrict__ ent = a.entries;
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
                 }
             }
         }
-        const bool last = !RESIDUAL && (tau == a.steps - 1);
+        const bool last = (RMODE != 1) && (tau == a.steps - 1);
 #pragma unroll
         for (int j = 0; j < 2 * PPT; ++j) {
             const float u = __builtin_fmaf(a.c, g[j], a.gamma * res[j]);
@@ -150,11 +152,12 @@ __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
         }
     }
 
-    if (RESIDUAL) {
+    if (RMODE != 0) {
         float *out = a.residual + (size_t)pair0 * 2;
 #pragma unroll
         for (int j = 0; j < 2 * PPT; ++j) out[j] = res[j];
-    } else {
+    }
+    if (RMODE != 1) {
         if (changed) {
 #pragma unroll
             for (int j = 0; j < PPT; ++j) raw.set_pair_bits(j, P::kBytesPerPair, P::pack(wq[2 * j], wq[2 * j + 1]));
@@ -175,17 +178,17 @@ __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
     }
 }
 
-template <int BITS, bool RESIDUAL, bool CLAMP, bool ANTI>
+template <int BITS, int RMODE, bool CLAMP, bool ANTI>
 void launch_ppt(const UpdateArgs &a, int ppt, unsigned blocks, hipStream_t s)
 {
     switch (ppt) {
-    case 4: update_kernel<BITS, 4, RESIDUAL, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
-    case 2: update_kernel<BITS, 2, RESIDUAL, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
-    default: update_kernel<BITS, 1, RESIDUAL, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
+    case 4: update_kernel<BITS, 4, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
+    case 2: update_kernel<BITS, 2, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
+    default: update_kernel<BITS, 1, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
     }
 }
 
-template <int BITS, bool RESIDUAL>
+template <int BITS, int RMODE>
 hipError_t launch_variant(const UpdateArgs &a, bool antithetic, hipStream_t s)
 {
     // Enough threads to fill 256 CUs x 4 SIMDs several waves deep, else fewer pairs per thread.
@@ -197,23 +200,26 @@ hipError_t launch_variant(const UpdateArgs &a, bool antithetic, hipStream_t s)
     // |sigma*eps| <= 1.2 * 5.77 < 7: the 4-bit container clamp cannot fire and is compiled out
     const bool clamp = !(a.sigma <= 1.2f);
     if (clamp) {
-        if (antithetic) launch_ppt<BITS, RESIDUAL, true, true>(a, ppt, blocks, s);
-        else launch_ppt<BITS, RESIDUAL, true, false>(a, ppt, blocks, s);
+        if (antithetic) launch_ppt<BITS, RMODE, true, true>(a, ppt, blocks, s);
+        else launch_ppt<BITS, RMODE, true, false>(a, ppt, blocks, s);
     } else {
-        if (antithetic) launch_ppt<BITS, RESIDUAL, false, true>(a, ppt, blocks, s);
-        else launch_ppt<BITS, RESIDUAL, false, false>(a, ppt, blocks, s);
+        if (antithetic) launch_ppt<BITS, RMODE, false, true>(a, ppt, blocks, s);
+        else launch_ppt<BITS, RMODE, false, false>(a, ppt, blocks, s);
     }
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_update(const UpdateArgs &a, int bits, bool residual, bool antithetic, hipStream_t s)
+hipError_t launch_update(const UpdateArgs &a, int bits, int rmode, bool antithetic, hipStream_t s)
 {
     if (a.n_pairs == 0) return hipSuccess;
-    if (bits == 4)
-        return residual ? launch_variant<4, true>(a, antithetic, s) : launch_variant<4, false>(a, antithetic, s);
-    return residual ? launch_variant<8, true>(a, antithetic, s) : launch_variant<8, false>(a, antithetic, s);
+    if (bits == 4) {
+        if (rmode == 0) return launch_variant<4, 0>(a, antithetic, s);
+        return rmode == 1 ? launch_variant<4, 1>(a, antithetic, s) : launch_variant<4, 2>(a, antithetic, s);
+    }
+    if (rmode == 0) return launch_variant<8, 0>(a, antithetic, s);
+    return rmode == 1 ? launch_variant<8, 1>(a, antithetic, s) : launch_variant<8, 2>(a, antithetic, s);
 }
 
 }  // namespace qes

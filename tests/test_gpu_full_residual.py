@@ -1,0 +1,76 @@
+"""GPU parity for the Full-Residual variant (paper Alg. 1, Eq. 6-8 with a stored residual) and the
+on-device fidelity check of §4.4: replayed residual (Alg. 2) against the stored one."""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env(oracle):
+    import torch
+    import paper_2602_03120_amd as qes
+    import gpu_util
+    assert torch.cuda.is_available()
+    return dict(torch=torch, qes=qes, u=gpu_util, oracle=oracle)
+
+
+@pytest.mark.parametrize("bits,out_f,in_f,N,steps", [(4, 256, 256, 8, 6), (8, 1024, 1024, 5, 3), (4, 33, 70, 30, 4),
+                                                     (4, 2048, 1024, 4, 2)])
+def test_steps_match_oracle(env, bits, out_f, in_f, N, steps):
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    qw, _, qmin, qmax = wl.random_tensor(500 + out_f, out_f, in_f, bits, 0)
+    ot = oracle.Tensor(qw, None, out_f, in_f, bits, 0, qmin, qmax, 21)
+    dt = u.device_tensor(ot)
+    rng = np.random.default_rng(out_f)
+    seeds = rng.integers(0, 2 ** 63, size=(steps, N), dtype=np.uint64)
+    fit = np.stack([oracle.normalize_fitness(rng.standard_normal(N).astype(np.float32)) for _ in range(steps)])
+    e_ref = np.zeros((out_f, in_f), dtype=np.float32)
+    e_dev = torch.zeros((out_f, in_f), dtype=torch.float32, device=u.DEV)
+    stats = torch.zeros(2, dtype=torch.int64, device=u.DEV)
+    ref_stats = np.zeros(2, dtype=np.uint64)
+    for t in range(steps):
+        qes.update_full_residual(dt, seeds[t], fit[t], 1.0, 1.5, 0.9, e_dev, stats=stats)
+        _, ref_stats = oracle.update_full_residual(ot, seeds[t], fit[t], 1.0, 1.5, 0.9, e_ref, stats=ref_stats)
+        assert (dt.qweight.cpu().numpy().view(np.uint8) == ot.qweight.view(np.uint8)).all(), t
+        assert (e_dev.cpu().numpy().view(np.uint32) == e_ref.view(np.uint32)).all(), t
+    assert (stats.cpu().numpy().view(np.uint64) == ref_stats).all() and ref_stats[0] > 0
+    assert np.abs(e_ref).max() > 0
+
+
+def test_replay_tracks_stored_residual_on_device(env):
+    """Interior weights (no gate can fire): after every step the residual replayed from the whole
+    history equals the stored one bit for bit, and Alg. 2 applies the same weight updates as Alg. 1."""
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    out_f, in_f, N, steps = 128, 256, 8, 8
+    q = np.random.default_rng(1).integers(-2, 3, size=(out_f, in_f)).astype(np.int8)
+    full = u.device_tensor(oracle.Tensor(q.copy(), None, out_f, in_f, 8, 0, -127, 127, 5))
+    rep = u.device_tensor(oracle.Tensor(q.copy(), None, out_f, in_f, 8, 0, -127, 127, 5))
+    rng = np.random.default_rng(2)
+    seeds = rng.integers(0, 2 ** 63, size=(steps, N), dtype=np.uint64)
+    fit = np.stack([qes.normalize_fitness(rng.standard_normal(N).astype(np.float32)) for _ in range(steps)])
+    e_dev = torch.zeros((out_f, in_f), dtype=torch.float32, device=u.DEV)
+    r_dev = torch.empty((out_f, in_f), dtype=torch.float32, device=u.DEV)
+    moved = 0
+    for t in range(steps):
+        qes.replay_residual(rep, seeds[:t], fit[:t], N, 1.0, 1.5, 0.9, r_dev)
+        assert torch.equal(r_dev.view(torch.int32), e_dev.view(torch.int32)), t
+        before = full.qweight.clone()
+        qes.update_full_residual(full, seeds[t], fit[t], 1.0, 1.5, 0.9, e_dev)
+        qes.update(rep, seeds[t], fit[t], seeds[:t], fit[:t], 1.0, 1.5, 0.9)
+        assert torch.equal(full.qweight, rep.qweight), t
+        moved += int((full.qweight != before).sum().item())
+    assert moved > 100
+
+
+def test_full_residual_argument_errors(env):
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    qw, _, qmin, qmax = wl.random_tensor(1, 16, 32, 4, 0)
+    dt = u.device_tensor(oracle.Tensor(qw, None, 16, 32, 4, 0, qmin, qmax, 1))
+    e = torch.zeros((16, 32), dtype=torch.float32, device=u.DEV)
+    with pytest.raises(qes.QesError):
+        qes.update_full_residual(dt, np.arange(4, dtype=np.uint64), np.zeros(4, np.float32), 0.0, 0.5, 0.9, e)
+    with pytest.raises(ValueError):
+        qes.update_full_residual(dt, np.arange(4, dtype=np.uint64), np.zeros(4, np.float32), 1.0, 0.5, 0.9, e.cpu())
