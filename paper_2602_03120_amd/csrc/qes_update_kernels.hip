@@ -95,8 +95,11 @@ struct Raw {
 
 // RMODE 0: Alg. 2 (replay + update in place). 1: replay only, residual written. 2: Alg. 1 step with a
 // stored residual (read, advanced one generation, written back together with the weights).
-template <int BITS, int PPT, int RMODE, bool CLAMP, bool ANTI>
-__global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
+// A thread owns PPT pairs and regenerates the noise of MI members at a time; PPT*MI = 4 independent
+// Philox/Box-Muller chains are in flight per thread whatever the split, and the sum of Eq. 5 still
+// runs in member order. Small PPT makes waves short, which evens out the last round of a launch.
+template <int BITS, int PPT, int MI, int RMODE, bool CLAMP, bool ANTI>
+__global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs a)
 {
     using P = Pack<BITS>;
     constexpr int kBytes = PPT * P::kBytesPerPair;
@@ -120,21 +123,39 @@ __global__ __launch_bounds__(kBlock) void update_kernel(const UpdateArgs a)
         float g[2 * PPT];
 #pragma unroll
         for (int j = 0; j < 2 * PPT; ++j) g[j] = 0.0f;
-        for (int32_t i = 0; i < a.N; ++i) {
-            const Entry en = ent[tau * a.N + i];          // wave-uniform: scalar load
+        const Entry *__restrict__ gen = ent + (size_t)tau * a.N;
+        // one member: its draws for this thread's pairs, added to g
+        auto accumulate = [&](const Entry &en, const float (&d)[2 * PPT]) {
             const float fit = __uint_as_float(en.fit_bits);
             const float fit_mirror = __uint_as_float(en.pad);   // antithetic pairs: fitness of the -δ member
 #pragma unroll
-            for (int j = 0; j < PPT; ++j) {
-                float d0, d1;
-                delta_pair_f32<CLAMP>(en.seed_lo, en.seed_hi, a.tensor_id, pair0 + j, a.sigma, d0, d1);
-                g[2 * j] = __builtin_fmaf(fit, d0, g[2 * j]);
-                g[2 * j + 1] = __builtin_fmaf(fit, d1, g[2 * j + 1]);
-                if (ANTI) {   // one draw serves members 2i (+δ) and 2i+1 (-δ), summed in member order
-                    g[2 * j] = __builtin_fmaf(fit_mirror, -d0, g[2 * j]);
-                    g[2 * j + 1] = __builtin_fmaf(fit_mirror, -d1, g[2 * j + 1]);
-                }
+            for (int j = 0; j < 2 * PPT; ++j) {
+                g[j] = __builtin_fmaf(fit, d[j], g[j]);
+                // one draw serves members 2i (+δ) and 2i+1 (-δ), summed in member order
+                if (ANTI) g[j] = __builtin_fmaf(fit_mirror, -d[j], g[j]);
             }
+        };
+        auto draw = [&](const Entry &en, float (&d)[2 * PPT]) {
+#pragma unroll
+            for (int j = 0; j < PPT; ++j)
+                delta_pair_f32<CLAMP>(en.seed_lo, en.seed_hi, a.tensor_id, pair0 + j, a.sigma, d[2 * j], d[2 * j + 1]);
+        };
+        int32_t i = 0;
+        for (; i + MI <= a.N; i += MI) {
+            Entry en[MI];                                 // wave-uniform: scalar loads
+            float d[MI][2 * PPT];
+#pragma unroll
+            for (int m = 0; m < MI; ++m) en[m] = gen[i + m];
+#pragma unroll
+            for (int m = 0; m < MI; ++m) draw(en[m], d[m]);
+#pragma unroll
+            for (int m = 0; m < MI; ++m) accumulate(en[m], d[m]);
+        }
+        for (; i < a.N; ++i) {                            // N % MI leftover members
+            const Entry en = gen[i];
+            float d[2 * PPT];
+            draw(en, d);
+            accumulate(en, d);
         }
         const bool last = (RMODE != 1) && (tau == a.steps - 1);
 #pragma unroll
@@ -182,19 +203,42 @@ template <int BITS, int RMODE, bool CLAMP, bool ANTI>
 void launch_ppt(const UpdateArgs &a, int ppt, unsigned blocks, hipStream_t s)
 {
     switch (ppt) {
-    case 4: update_kernel<BITS, 4, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
-    case 2: update_kernel<BITS, 2, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
-    default: update_kernel<BITS, 1, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
+    case 4: update_kernel<BITS, 4, 1, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
+    case 2: update_kernel<BITS, 2, 2, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
+    default: update_kernel<BITS, 1, 4, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
     }
+}
+
+// Relative duration of a launch of `waves` waves whose work is proportional to ppt, on 1024 SIMDs
+// holding 8 waves each: whole rounds run at full rate; the waves left over run at the rate a SIMD
+// reaches with that few waves (measured with the noise loop: 1 wave 49 %, 2 waves 73 %, 4 waves
+// 93 % of the 8-wave rate).
+double launch_cost(uint64_t n_pairs, int ppt)
+{
+    const double x = (double)((n_pairs / ppt + 63) / 64) / (1024.0 * 8.0);
+    const double full = (double)(uint64_t)x;
+    const double f = x - full;
+    double tail = 0.0;
+    if (f > 0.0) {
+        const double pts[5][2] = {{0.0, 0.255}, {0.125, 0.255}, {0.25, 0.34}, {0.5, 0.54}, {1.0, 1.0}};
+        for (int k = 0; k < 4; ++k)
+            if (f >= pts[k][0] && f <= pts[k + 1][0])
+                tail = pts[k][1] + (pts[k + 1][1] - pts[k][1]) * (f - pts[k][0]) / (pts[k + 1][0] - pts[k][0]);
+    }
+    return (full + tail) * ppt;
 }
 
 template <int BITS, int RMODE>
 hipError_t launch_variant(const UpdateArgs &a, bool antithetic, hipStream_t s)
 {
-    // Enough threads to fill 256 CUs x 4 SIMDs several waves deep, else fewer pairs per thread.
-    const uint64_t want_threads = 256ull * 4 * 64 * 4;
-    int ppt = 4;
-    while (ppt > 1 && ((a.n_pairs % ppt) != 0 || a.n_pairs / ppt < want_threads)) ppt >>= 1;
+    // pairs per thread: the split with the shortest predicted launch (ties go to the wider thread)
+    int ppt = 1;
+    double best = launch_cost(a.n_pairs, 1);
+    for (int cand = 2; cand <= 4; cand *= 2) {
+        if (a.n_pairs % cand) break;
+        const double c = launch_cost(a.n_pairs, cand);
+        if (c <= best) { best = c; ppt = cand; }
+    }
     const uint64_t threads = a.n_pairs / ppt;
     const unsigned blocks = (unsigned)((threads + kBlock - 1) / kBlock);
     // |sigma*eps| <= 1.2 * 5.77 < 7: the 4-bit container clamp cannot fire and is compiled out
