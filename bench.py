@@ -37,9 +37,9 @@ OPS_PER_MEMBER_ELEMENT_GEMM = 6.0      # Eq. 4 gate and the exact small-integer 
 MFMA_PEAK = {"bf16": 2.5e15, "i8": 5.0e15}
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this file, scaled by the same counters on the plain copy issued below (see
-# profiles/update_kernel_config2.md): {(config, tensor name): bytes}
-MEASURED_TRAFFIC_BYTES = {(2, "gate"): 2.36e6}
+# this file, scaled by the same counters on the plain copy issued below (see profiles/):
+# {(config, tensor name): bytes}. A launch covers one tensor, whatever --layers says.
+MEASURED_TRAFFIC_BYTES = {(2, "gate"): 2.374e6, (3, "gate"): 7.223e6}
 
 
 def parse():
@@ -194,7 +194,7 @@ def main():
             "kernel": "update_kernel (qes_update, %s %dx%d)" % (dom.name, dom.out_features, dom.in_features),
             "bound": "alu", "achieved": achieved_tops, "peak": VALU_PEAK_TOPS, "unit": "Tlane-op/s",
             "frac": achieved_tops / VALU_PEAK_TOPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.index, dom.name)) if n_layers == cfg.n_layers else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.index, dom.name)),
             "avg_launch_ms": dom_ms,
             "algorithmic_ops_per_launch": ops,
             "algorithmic_bytes_per_launch": dom_elems * cfg.bits / 8.0 * 2.0,
