@@ -25,7 +25,8 @@ def _history(rng, oracle, K, N):
 
 
 @pytest.mark.parametrize("bits,out_f,in_f,K,N,sigma", [(4, 256, 256, 4, 8, 1.0), (4, 33, 70, 3, 6, 1.0),
-                                                      (8, 1024, 1024, 2, 4, 1.0), (4, 2048, 1024, 1, 2, 2.5),
+                                                      (8, 1024, 1024, 2, 4, 1.0), (4, 2048, 1024, 1, 6, 2.5),
+                                                      (4, 1024, 4096, 1, 6, 1.0),
                                                       (4, 64, 128, 0, 30, 1.0)])
 def test_update_and_replay(env, bits, out_f, in_f, K, N, sigma):
     torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]

@@ -18,7 +18,7 @@ def env(oracle):
 
 
 @pytest.mark.parametrize("bits,out_f,in_f,N,steps", [(4, 256, 256, 8, 6), (8, 1024, 1024, 5, 3), (4, 33, 70, 30, 4),
-                                                     (4, 2048, 1024, 4, 2)])
+                                                     (4, 2048, 1024, 4, 2), (4, 1024, 4096, 3, 2)])
 def test_steps_match_oracle(env, bits, out_f, in_f, N, steps):
     torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
     qw, _, qmin, qmax = wl.random_tensor(500 + out_f, out_f, in_f, bits, 0)
