@@ -62,6 +62,12 @@ def lib():
         L.oracle_update.restype = i32
         L.oracle_update_full_residual.argtypes = [tp, vp, vp, i32, f32, f32, f32, vp, vp, vp]
         L.oracle_update_full_residual.restype = i32
+        L.oracle_update_full_residual_f16.argtypes = [tp, vp, vp, i32, f32, f32, f32, vp, vp]
+        L.oracle_update_full_residual_f16.restype = i32
+        L.oracle_f16_to_f32.argtypes = [ctypes.c_uint16]
+        L.oracle_f16_to_f32.restype = f32
+        L.oracle_f32_to_f16_sat.argtypes = [f32]
+        L.oracle_f32_to_f16_sat.restype = ctypes.c_uint16
         L.oracle_aggregate.argtypes = [tp, vp, vp, i32, f32, vp, i32]
         L.oracle_aggregate.restype = i32
         _LIB = L
@@ -251,6 +257,27 @@ def update_full_residual(w, seeds_t, fit_t, sigma, alpha, gamma, e_state, want_u
     _check(lib().oracle_update_full_residual(ctypes.byref(d), _ptr(seeds_t), _ptr(fit_t), N, sigma,
                                              alpha, gamma, _ptr(e_state), _ptr(u), _ptr(stats)))
     return u, stats
+
+
+def update_full_residual_f16(w, seeds_t, fit_t, sigma, alpha, gamma, e_state, stats=None):
+    """In-place Alg. 1 step on w.qweight and e_state (binary16 bit patterns, uint16 [out,in])."""
+    seeds_t = _c(seeds_t, np.uint64)
+    fit_t = _c(fit_t, np.float32)
+    assert e_state.dtype == np.uint16 and e_state.flags.c_contiguous
+    if stats is None:
+        stats = np.zeros(2, dtype=np.uint64)
+    d = w.desc()
+    _check(lib().oracle_update_full_residual_f16(ctypes.byref(d), _ptr(seeds_t), _ptr(fit_t), seeds_t.size, sigma,
+                                                 alpha, gamma, _ptr(e_state), _ptr(stats)))
+    return stats
+
+
+def f16_to_f32(h):
+    return float(lib().oracle_f16_to_f32(int(h)))
+
+
+def f32_to_f16_sat(f):
+    return int(lib().oracle_f32_to_f16_sat(float(f)))
 
 
 def aggregate(w, seeds, fit, sigma, antithetic=False):

@@ -614,6 +614,85 @@ int oracle_update_full_residual(oracle_tensor *w, const uint64_t *seeds_t, const
     return ORACLE_OK;
 }
 
+/*
+ * IEEE binary16 <-> binary32, written out (Alg. 1 initialises the residuals as FP16, and the
+ * Full-Residual variant of the residual ablation in §4 stores them so). Encoding rounds to nearest even after saturating at the largest finite
+ * half (±65504), so a stored residual is always finite; NaN does not occur (inputs are finite).
+ */
+float oracle_f16_to_f32(uint16_t h)
+{
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    const int32_t e = (h >> 10) & 0x1F;
+    const uint32_t m = h & 0x3FFu;
+    double v;
+    if (e == 0) v = ldexp((double)m, -24);                 /* zero and subnormals: m · 2^-24 */
+    else if (e == 31) v = m ? NAN : INFINITY;
+    else v = ldexp((double)(m | 0x400u), e - 25);          /* (1024+m) · 2^(e-15-10) */
+    float f = (float)v;                                    /* exact: 11 significant bits */
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u |= sign;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+uint16_t oracle_f32_to_f16_sat(float f)
+{
+    const double a = fabs((double)f);
+    const uint16_t sign = signbit(f) ? 0x8000u : 0u;
+    if (a >= 65504.0) return (uint16_t)(sign | 0x7BFFu);
+    if (a == 0.0) return sign;
+    /* spacing of halves around a: 2^(e-10) with e = floor(log2 a), never below 2^-24 */
+    int e;
+    (void)frexp(a, &e);                                    /* a = m·2^e, m in [0.5,1) -> floor(log2 a) = e-1 */
+    int q = (e - 1) - 10;
+    if (q < -24) q = -24;
+    const double steps = nearbyint(ldexp(a, -q));          /* ties to even in the default rounding mode */
+    const double r = ldexp(steps, q);                      /* the nearest half, as a double; r <= 65504 */
+    /* encode r exactly */
+    if (r == 0.0) return sign;
+    (void)frexp(r, &e);
+    const int eb = (e - 1) + 15;                           /* biased exponent */
+    if (eb <= 0) return (uint16_t)(sign | (uint16_t)ldexp(r, 24));          /* subnormal: r / 2^-24 */
+    const uint32_t mant = (uint32_t)ldexp(r, 10 - (e - 1)) - 1024u;
+    return (uint16_t)(sign | ((uint32_t)eb << 10) | mant);
+}
+
+/*
+ * Alg. 1 with the residual held in binary16: each step reads e as a half, computes in fp32 exactly
+ * as oracle_update_full_residual does, and stores e' = half(u - ΔW) (saturating, round to nearest
+ * even).
+ */
+int oracle_update_full_residual_f16(oracle_tensor *w, const uint64_t *seeds_t, const float *fit_t,
+                                    int32_t N, float sigma, float alpha, float gamma, uint16_t *e_state,
+                                    uint64_t *stats)
+{
+    if (!tensor_ok(w) || !seeds_t || !fit_t || !e_state || N <= 0 || !(sigma > 0.0f))
+        return ORACLE_ERR_INVALID_ARG;
+    const int64_t K = w->in_features;
+    const float c = step_coeff(alpha, N, sigma);
+    uint64_t changed = 0, gated = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : changed, gated)
+    for (int32_t n = 0; n < w->out_features; ++n) {
+        for (int64_t k = 0; k < K; k += 2) {
+            const uint64_t e0 = (uint64_t)((int64_t)n * K + k);
+            float g[2];
+            aggregate_pair(seeds_t, fit_t, N, w->tensor_id, e0 >> 1, sigma, 0, g);
+            for (int l = 0; l < 2; ++l) {
+                int32_t wq = load_q(w, n, k + l);
+                float u;
+                int32_t raw;
+                int32_t df = ef_step(c, g[l], gamma, oracle_f16_to_f32(e_state[e0 + l]), wq, w->qmin, w->qmax, &u, &raw);
+                e_state[e0 + l] = oracle_f32_to_f16_sat(u - (float)df);
+                if (df != 0) { store_q(w, n, k + l, wq + df); ++changed; }
+                else if (raw != 0) ++gated;
+            }
+        }
+    }
+    if (stats) { stats[0] += changed; stats[1] += gated; }
+    return ORACLE_OK;
+}
+
 /* g = Σ_i F_i δ_i per element (Eq. 5 without the 1/(Nσ) factor), for pins */
 int oracle_aggregate(const oracle_tensor *w, const uint64_t *seeds, const float *fit, int32_t N,
                      float sigma, float *g_out, int32_t antithetic)
