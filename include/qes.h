@@ -202,6 +202,16 @@ int qes_update_full_residual(qes_tensor *w, const uint64_t *seeds_t, const float
                              float alpha, float gamma, float *e_state, uint64_t *stats, void *stream);
 
 /*
+ * The same step with the residual stored as IEEE binary16, the precision Alg. 1 initialises it in
+ * (and the Full-Residual variant of the §4 residual ablation stores): e is decoded exactly, the
+ * step is computed in fp32 as above, and e ← half(u − Δf), rounded to nearest even after
+ * saturating at ±65504, so a stored residual is always finite.
+ * e_state_f16: DEVICE binary16 [out_features, in_features], 16-byte aligned, read and written.
+ */
+int qes_update_full_residual_f16(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, int32_t N, float sigma,
+                                 float alpha, float gamma, uint16_t *e_state_f16, uint64_t *stats, void *stream);
+
+/*
  * Alg. 1 "normalize reward for population": z-score with the population standard deviation,
  * computed in fp64; zero variance or N < 2 gives all zeros. HOST in, HOST out, no GPU work.
  */

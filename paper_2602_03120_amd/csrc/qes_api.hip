@@ -138,7 +138,7 @@ int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit
     if (N <= 0 || N > QES_MAX_POPULATION || hist_len < 0 || hist_len > QES_MAX_HISTORY) return QES_ERR_INVALID_ARG;
     if (antithetic && (N & 1)) return QES_ERR_INVALID_ARG;
     const bool replay_only = (rmode == 1);
-    if (rmode == 2 && hist_len != 0) return QES_ERR_INVALID_ARG;
+    if (rmode >= 2 && hist_len != 0) return QES_ERR_INVALID_ARG;
     if (hist_len > 0 && (!hist_seeds || !hist_fit)) return QES_ERR_INVALID_ARG;
     if (!replay_only && (!seeds_t || !fit_t)) return QES_ERR_INVALID_ARG;
     if (rmode != 0 && (!residual || ((uintptr_t)residual & 15u) != 0)) return QES_ERR_INVALID_ARG;
@@ -374,6 +374,13 @@ int qes_update_full_residual(qes_tensor *w, const uint64_t *seeds_t, const float
 {
     return update_common(w, seeds_t, fit_t, nullptr, nullptr, 0, N, sigma, alpha, gamma, stats, e_state, 2, false,
                          stream);
+}
+
+int qes_update_full_residual_f16(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, int32_t N, float sigma,
+                                 float alpha, float gamma, uint16_t *e_state_f16, uint64_t *stats, void *stream)
+{
+    return update_common(w, seeds_t, fit_t, nullptr, nullptr, 0, N, sigma, alpha, gamma, stats, (float *)e_state_f16, 3,
+                         false, stream);
 }
 
 int qes_normalize_fitness(const float *reward, int32_t N, float *fit)

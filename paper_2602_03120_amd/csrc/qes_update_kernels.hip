@@ -94,7 +94,9 @@ struct Raw {
 };
 
 // RMODE 0: Alg. 2 (replay + update in place). 1: replay only, residual written. 2: Alg. 1 step with a
-// stored residual (read, advanced one generation, written back together with the weights).
+// stored residual (read, advanced one generation, written back together with the weights). 3: the
+// same with the residual stored as binary16 (decoded exactly, arithmetic in fp32, encoded with
+// round-to-nearest-even after saturating at the largest finite half).
 // A thread owns PPT pairs and regenerates the noise of MI members at a time; PPT*MI = 4 independent
 // Philox/Box-Muller chains are in flight per thread whatever the split, and the sum of Eq. 5 still
 // runs in member order. Small PPT makes waves short, which evens out the last round of a launch.
@@ -115,7 +117,11 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs a)
 
     float res[2 * PPT];
 #pragma unroll
-    for (int j = 0; j < 2 * PPT; ++j) res[j] = (RMODE == 2) ? a.residual[(size_t)pair0 * 2 + j] : 0.0f;
+    for (int j = 0; j < 2 * PPT; ++j) {
+        if (RMODE == 2) res[j] = a.residual[(size_t)pair0 * 2 + j];
+        else if (RMODE == 3) res[j] = (float)((const _Float16 *)a.residual)[(size_t)pair0 * 2 + j];
+        else res[j] = 0.0f;
+    }
 
     uint32_t changed = 0, gated = 0;
     const Entry *__restrict__ ent = a.entries;
@@ -173,10 +179,15 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs a)
         }
     }
 
-    if (RMODE != 0) {
+    if (RMODE == 1 || RMODE == 2) {
         float *out = a.residual + (size_t)pair0 * 2;
 #pragma unroll
         for (int j = 0; j < 2 * PPT; ++j) out[j] = res[j];
+    }
+    if (RMODE == 3) {
+        _Float16 *out = (_Float16 *)a.residual + (size_t)pair0 * 2;
+#pragma unroll
+        for (int j = 0; j < 2 * PPT; ++j) out[j] = (_Float16)fminf(fmaxf(res[j], -65504.0f), 65504.0f);
     }
     if (RMODE != 1) {
         if (changed) {
@@ -259,11 +270,19 @@ hipError_t launch_update(const UpdateArgs &a, int bits, int rmode, bool antithet
 {
     if (a.n_pairs == 0) return hipSuccess;
     if (bits == 4) {
-        if (rmode == 0) return launch_variant<4, 0>(a, antithetic, s);
-        return rmode == 1 ? launch_variant<4, 1>(a, antithetic, s) : launch_variant<4, 2>(a, antithetic, s);
+        switch (rmode) {
+        case 0: return launch_variant<4, 0>(a, antithetic, s);
+        case 1: return launch_variant<4, 1>(a, antithetic, s);
+        case 2: return launch_variant<4, 2>(a, antithetic, s);
+        default: return launch_variant<4, 3>(a, antithetic, s);
+        }
     }
-    if (rmode == 0) return launch_variant<8, 0>(a, antithetic, s);
-    return rmode == 1 ? launch_variant<8, 1>(a, antithetic, s) : launch_variant<8, 2>(a, antithetic, s);
+    switch (rmode) {
+    case 0: return launch_variant<8, 0>(a, antithetic, s);
+    case 1: return launch_variant<8, 1>(a, antithetic, s);
+    case 2: return launch_variant<8, 2>(a, antithetic, s);
+    default: return launch_variant<8, 3>(a, antithetic, s);
+    }
 }
 
 }  // namespace qes

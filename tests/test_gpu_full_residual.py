@@ -74,3 +74,35 @@ def test_full_residual_argument_errors(env):
         qes.update_full_residual(dt, np.arange(4, dtype=np.uint64), np.zeros(4, np.float32), 0.0, 0.5, 0.9, e)
     with pytest.raises(ValueError):
         qes.update_full_residual(dt, np.arange(4, dtype=np.uint64), np.zeros(4, np.float32), 1.0, 0.5, 0.9, e.cpu())
+
+
+@pytest.mark.parametrize("bits,out_f,in_f,N,steps,alpha", [(4, 256, 256, 8, 6, 1.5), (8, 1024, 1024, 5, 3, 1.5),
+                                                           (4, 33, 70, 30, 4, 1.5), (4, 2048, 1024, 4, 2, 1.5),
+                                                           (4, 1024, 4096, 3, 2, 1.5),
+                                                           (4, 64, 64, 6, 3, 3e6)])   # huge steps: gated residuals saturate
+def test_half_precision_residual_steps_match_oracle(env, bits, out_f, in_f, N, steps, alpha):
+    """The residual held as binary16 (Alg. 1's initialisation): weights, residual bit patterns and
+    counters equal the oracle's, step after step; the last case drives gated residuals into the
+    saturation of the encoding."""
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    qw, _, qmin, qmax = wl.random_tensor(600 + out_f, out_f, in_f, bits, 0)
+    ot = oracle.Tensor(qw, None, out_f, in_f, bits, 0, qmin, qmax, 22)
+    dt = u.device_tensor(ot)
+    rng = np.random.default_rng(out_f + 1)
+    seeds = rng.integers(0, 2 ** 63, size=(steps, N), dtype=np.uint64)
+    fit = np.stack([oracle.normalize_fitness(rng.standard_normal(N).astype(np.float32)) for _ in range(steps)])
+    e_ref = np.zeros((out_f, in_f), dtype=np.uint16)
+    e_dev = torch.zeros((out_f, in_f), dtype=torch.float16, device=u.DEV)
+    stats = torch.zeros(2, dtype=torch.int64, device=u.DEV)
+    ref_stats = np.zeros(2, dtype=np.uint64)
+    for t in range(steps):
+        qes.update_full_residual(dt, seeds[t], fit[t], 1.0, alpha, 0.9, e_dev, stats=stats, half=True)
+        ref_stats = oracle.update_full_residual_f16(ot, seeds[t], fit[t], 1.0, alpha, 0.9, e_ref, stats=ref_stats)
+        assert (dt.qweight.cpu().numpy().view(np.uint8) == ot.qweight.view(np.uint8)).all(), t
+        assert (e_dev.view(torch.int16).cpu().numpy().view(np.uint16) == e_ref).all(), t
+    assert (stats.cpu().numpy().view(np.uint64) == ref_stats).all()
+    assert (e_ref != 0).any()
+    if alpha > 1e3:
+        assert ((e_ref & 0x7FFF) == 0x7BFF).any()      # some residual sits at the largest finite half
+    else:
+        assert ref_stats[0] > 0
