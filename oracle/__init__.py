@@ -62,6 +62,8 @@ def lib():
         L.oracle_update.restype = i32
         L.oracle_update_full_residual.argtypes = [tp, vp, vp, i32, f32, f32, f32, vp, vp, vp]
         L.oracle_update_full_residual.restype = i32
+        L.oracle_update_stochastic_rounding.argtypes = [tp, vp, vp, i32, f32, f32, u64, vp, vp, i32]
+        L.oracle_update_stochastic_rounding.restype = i32
         L.oracle_update_full_residual_f16.argtypes = [tp, vp, vp, i32, f32, f32, f32, vp, vp]
         L.oracle_update_full_residual_f16.restype = i32
         L.oracle_f16_to_f32.argtypes = [ctypes.c_uint16]
@@ -269,6 +271,20 @@ def update_full_residual_f16(w, seeds_t, fit_t, sigma, alpha, gamma, e_state, st
     d = w.desc()
     _check(lib().oracle_update_full_residual_f16(ctypes.byref(d), _ptr(seeds_t), _ptr(fit_t), seeds_t.size, sigma,
                                                  alpha, gamma, _ptr(e_state), _ptr(stats)))
+    return stats
+
+
+def update_stochastic_rounding(w, seeds_t, fit_t, sigma, alpha, round_seed, stats=None, rows=None):
+    """In-place stateless step with stochastic rounding of the update (baseline of the paper's §5)."""
+    seeds_t = _c(seeds_t, np.uint64)
+    fit_t = _c(fit_t, np.float32)
+    if stats is None:
+        stats = np.zeros(2, dtype=np.uint64)
+    rows_a = None if rows is None else _c(rows, np.int32)
+    d = w.desc()
+    _check(lib().oracle_update_stochastic_rounding(ctypes.byref(d), _ptr(seeds_t), _ptr(fit_t), seeds_t.size, sigma,
+                                                   alpha, int(round_seed), _ptr(stats), _ptr(rows_a),
+                                                   0 if rows_a is None else rows_a.size))
     return stats
 
 

@@ -615,6 +615,53 @@ int oracle_update_full_residual(oracle_tensor *w, const uint64_t *seeds_t, const
 }
 
 /*
+ * Stateless baseline of §5 (W ← W + Q(α ĝ) with a stochastic Q; the rule the paper attributes to
+ * QuZO-style training): no residual; Δ = ⌊u⌋ + [ub < u − ⌊u⌋] with u = c·g and ub the element's
+ * rounding uniform of the step (N8: Philox keyed by round_seed, stream tag 1, words 2 and 3); the
+ * range gate is Eq. 4's (masked). Unbiased per step, E[Δ] = u, but the errors do not cancel over
+ * steps.
+ */
+int oracle_update_stochastic_rounding(oracle_tensor *w, const uint64_t *seeds_t, const float *fit_t,
+                                      int32_t N, float sigma, float alpha, uint64_t round_seed,
+                                      uint64_t *stats, const int32_t *rows, int32_t n_rows)
+{
+    if (!tensor_ok(w) || !seeds_t || !fit_t || N <= 0 || !(sigma > 0.0f)) return ORACLE_ERR_INVALID_ARG;
+    const int64_t K = w->in_features;
+    const int32_t nsel = rows ? n_rows : w->out_features;
+    const float c = step_coeff(alpha, N, sigma);
+    const uint32_t key[2] = { (uint32_t)(round_seed & 0xFFFFFFFFu), (uint32_t)(round_seed >> 32) };
+    uint64_t changed = 0, gated = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : changed, gated)
+    for (int32_t r = 0; r < nsel; ++r) {
+        const int64_t n = rows ? rows[r] : r;
+        for (int64_t k = 0; k < K; k += 2) {
+            const uint64_t pair = (uint64_t)(n * K + k) >> 1;
+            float g[2];
+            aggregate_pair(seeds_t, fit_t, N, w->tensor_id, pair, sigma, 0, g);
+            const uint32_t ctr[4] = { (uint32_t)(pair & 0xFFFFFFFFu), (uint32_t)(pair >> 32), w->tensor_id, 1u };
+            uint32_t words[4];
+            oracle_philox4x32_10(ctr, key, words);
+            for (int l = 0; l < 2; ++l) {
+                const int32_t wq = load_q(w, n, k + l);
+                const float u = c * g[l];
+                const float ub = (float)(words[2 + l] >> 8) * 0x1p-24f;
+                const float fl = floorf(u);
+                const float fr = u - fl;
+                const int32_t d = sat_i32(fl) + ((ub < fr) ? 1 : 0);
+                const int64_t v = (int64_t)wq + (int64_t)d;
+                if (v >= w->qmin && v <= w->qmax) {
+                    if (d != 0) { store_q(w, n, k + l, (int32_t)v); ++changed; }
+                } else {
+                    ++gated;
+                }
+            }
+        }
+    }
+    if (stats) { stats[0] += changed; stats[1] += gated; }
+    return ORACLE_OK;
+}
+
+/*
  * IEEE binary16 <-> binary32, written out (Alg. 1 initialises the residuals as FP16, and the
  * Full-Residual variant of the residual ablation in §4 stores them so). Encoding rounds to nearest even after saturating at the largest finite
  * half (±65504), so a stored residual is always finite; NaN does not occur (inputs are finite).
