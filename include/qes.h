@@ -212,6 +212,17 @@ int qes_update_full_residual_f16(qes_tensor *w, const uint64_t *seeds_t, const f
                                  float alpha, float gamma, uint16_t *e_state_f16, uint64_t *stats, void *stream);
 
 /*
+ * Stateless baseline the paper's §5 analyses (W ← W + Q(α ĝ), Eq. 9-10, with a stochastic Q), for
+ * comparisons on the same kernels; not part of QES. No residual and no history:
+ *   g = Σ_i fit_t[i]·δ(seeds_t[i]);  u = c·g;  Δ = ⌊u⌋ + [ub < u − ⌊u⌋];  W ← W + Δ if in range else W
+ * with ub the element's rounding uniform of this step (docs/NOISE_SPEC.md N8: Philox keyed by
+ * round_seed, stream tag 1). The deterministic stateless baseline is qes_update with hist_len = 0.
+ * Other arguments as for qes_update.
+ */
+int qes_update_stochastic_rounding(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, int32_t N, float sigma,
+                                   float alpha, uint64_t round_seed, uint64_t *stats, void *stream);
+
+/*
  * Alg. 1 "normalize reward for population": z-score with the population standard deviation,
  * computed in fp64; zero variance or N < 2 gives all zeros. HOST in, HOST out, no GPU work.
  */

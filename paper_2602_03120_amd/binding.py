@@ -64,6 +64,7 @@ def _load():
         "qes_replay_residual_antithetic": ([tp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
         "qes_update_full_residual": ([tp, vp, vp, i32, f32, f32, f32, vp, vp, vp], i32),
         "qes_update_full_residual_f16": ([tp, vp, vp, i32, f32, f32, f32, vp, vp, vp], i32),
+        "qes_update_stochastic_rounding": ([tp, vp, vp, i32, f32, f32, u64, vp, vp], i32),
         "qes_normalize_fitness": ([vp, i32, vp], i32),
         "qes_bench_noise": ([i32, u64, i32, f32, vp, vp], i32),
         "qes_bench_copy": ([vp, vp, sz, vp], i32),
@@ -82,7 +83,7 @@ def _load():
 EXPORTS = ["qes_noise_words", "qes_noise_gauss", "qes_noise_delta", "qes_noise_from_words", "qes_perturbed_qgemm",
            "qes_perturbed_qgemm_antithetic", "qes_gemm_workspace_bytes", "qes_update", "qes_update_antithetic",
            "qes_replay_residual", "qes_replay_residual_antithetic", "qes_update_full_residual", "qes_update_full_residual_f16",
-           "qes_normalize_fitness",
+           "qes_update_stochastic_rounding", "qes_normalize_fitness",
            "qes_bench_noise", "qes_bench_copy", "qes_status_string", "qes_last_hip_error",
            "qes_abi_version"]
 
@@ -237,6 +238,19 @@ def update_full_residual(w, seeds_t, fit_t, sigma, alpha, gamma, e_state, stats=
     name = "qes_update_full_residual_f16" if half else "qes_update_full_residual"
     _check(getattr(_load(), name)(ctypes.byref(d), _hptr(seeds_t), _hptr(fit_t), N, sigma, alpha, gamma,
                                   _dev_ptr(e_state, "e_state"), _dev_ptr(stats, "stats"), _stream(stream)), name)
+
+
+def update_stochastic_rounding(w, seeds_t, fit_t, sigma, alpha, round_seed, stats=None, stream=None):
+    """One stateless step with stochastic rounding of the update (baseline), in place on w.qweight."""
+    seeds_t = _host(seeds_t, np.uint64)
+    fit_t = _host(fit_t, np.float32)
+    N = int(fit_t.size)
+    if seeds_t.size != N:
+        raise ValueError("seeds_t and fit_t differ in length")
+    d = w.desc()
+    _check(_load().qes_update_stochastic_rounding(ctypes.byref(d), _hptr(seeds_t), _hptr(fit_t), N, sigma, alpha,
+                                                  int(round_seed), _dev_ptr(stats, "stats"), _stream(stream)),
+           "qes_update_stochastic_rounding")
 
 
 def normalize_fitness(reward):

@@ -131,7 +131,7 @@ int fill_entries(qes::Entry *dst, const uint64_t *seeds_t, const float *fit_t, c
 
 int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
                   const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
-                  uint64_t *stats, float *residual, int rmode, bool antithetic, void *stream)
+                  uint64_t *stats, float *residual, int rmode, bool antithetic, void *stream, uint64_t round_seed = 0)
 {
     int rc = tensor_check(w);
     if (rc != QES_OK) return rc;
@@ -141,7 +141,7 @@ int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit
     if (rmode >= 2 && hist_len != 0) return QES_ERR_INVALID_ARG;
     if (hist_len > 0 && (!hist_seeds || !hist_fit)) return QES_ERR_INVALID_ARG;
     if (!replay_only && (!seeds_t || !fit_t)) return QES_ERR_INVALID_ARG;
-    if (rmode != 0 && (!residual || ((uintptr_t)residual & 15u) != 0)) return QES_ERR_INVALID_ARG;
+    if (rmode != 0 && rmode != 4 && (!residual || ((uintptr_t)residual & 15u) != 0)) return QES_ERR_INVALID_ARG;
     if (!(sigma > 0.0f) || !std::isfinite(sigma) || !std::isfinite(alpha)) return QES_ERR_INVALID_ARG;
     if (!(gamma >= 0.0f && gamma <= 1.0f)) return QES_ERR_INVALID_ARG;
     if (stats && ((uintptr_t)stats & 7u) != 0) return QES_ERR_INVALID_ARG;
@@ -166,6 +166,8 @@ int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit
     a.qmin = w->qmin;
     a.qspan = (uint32_t)(w->qmax - w->qmin);
     a.tensor_id = w->tensor_id;
+    a.round_k0 = (uint32_t)round_seed;
+    a.round_k1 = (uint32_t)(round_seed >> 32);
 
     std::lock_guard<std::mutex> lock(g_mu);
     Slot *slot = nullptr;
@@ -381,6 +383,13 @@ int qes_update_full_residual_f16(qes_tensor *w, const uint64_t *seeds_t, const f
 {
     return update_common(w, seeds_t, fit_t, nullptr, nullptr, 0, N, sigma, alpha, gamma, stats, (float *)e_state_f16, 3,
                          false, stream);
+}
+
+int qes_update_stochastic_rounding(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, int32_t N, float sigma,
+                                   float alpha, uint64_t round_seed, uint64_t *stats, void *stream)
+{
+    return update_common(w, seeds_t, fit_t, nullptr, nullptr, 0, N, sigma, alpha, 0.0f, stats, nullptr, 4, false,
+                         stream, round_seed);
 }
 
 int qes_normalize_fitness(const float *reward, int32_t N, float *fit)

@@ -25,6 +25,7 @@ struct UpdateArgs {
     int32_t qmin;
     uint32_t qspan;              // qmax - qmin
     uint32_t tensor_id;
+    uint32_t round_k0, round_k1; // stochastic-rounding baseline: key of the step's rounding stream
 };
 
 struct GemmArgs {

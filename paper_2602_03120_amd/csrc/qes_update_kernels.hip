@@ -96,7 +96,9 @@ struct Raw {
 // RMODE 0: Alg. 2 (replay + update in place). 1: replay only, residual written. 2: Alg. 1 step with a
 // stored residual (read, advanced one generation, written back together with the weights). 3: the
 // same with the residual stored as binary16 (decoded exactly, arithmetic in fp32, encoded with
-// round-to-nearest-even after saturating at the largest finite half).
+// round-to-nearest-even after saturating at the largest finite half). 4: the stateless baseline of
+// §5, W <- W + Q(c g) with stochastic rounding Q (no residual; rounding uniforms from the Philox
+// stream keyed by the step's rounding seed, stream tag 1).
 // A thread owns PPT pairs and regenerates the noise of MI members at a time; PPT*MI = 4 independent
 // Philox/Box-Muller chains are in flight per thread whatever the split, and the sum of Eq. 5 still
 // runs in member order. Small PPT makes waves short, which evens out the last round of a launch.
@@ -164,10 +166,28 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs a)
             accumulate(en, d);
         }
         const bool last = (RMODE != 1) && (tau == a.steps - 1);
+        uint32_t round_word[2 * PPT];
+        if (RMODE == 4) {
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) {
+                const Words rw = philox4x32_10(pair0 + j, 0u, a.tensor_id, 1u, a.round_k0, a.round_k1);
+                round_word[2 * j] = rw.w2;
+                round_word[2 * j + 1] = rw.w3;
+            }
+        }
 #pragma unroll
         for (int j = 0; j < 2 * PPT; ++j) {
-            const float u = __builtin_fmaf(a.c, g[j], a.gamma * res[j]);
-            const int32_t d = (int32_t)__builtin_rintf(u);
+            float u;
+            int32_t d;
+            if (RMODE == 4) {
+                u = a.c * g[j];
+                const float fl = __builtin_floorf(u);
+                const float ub = (float)(round_word[j] >> 8) * 0x1p-24f;
+                d = (int32_t)fl + ((ub < u - fl) ? 1 : 0);
+            } else {
+                u = __builtin_fmaf(a.c, g[j], a.gamma * res[j]);
+                d = (int32_t)__builtin_rintf(u);
+            }
             const int32_t nv = gate(wq[j], d, a.qmin, a.qspan);
             const int32_t df = nv - wq[j];
             res[j] = u - (float)df;
@@ -274,14 +294,16 @@ hipError_t launch_update(const UpdateArgs &a, int bits, int rmode, bool antithet
         case 0: return launch_variant<4, 0>(a, antithetic, s);
         case 1: return launch_variant<4, 1>(a, antithetic, s);
         case 2: return launch_variant<4, 2>(a, antithetic, s);
-        default: return launch_variant<4, 3>(a, antithetic, s);
+        case 3: return launch_variant<4, 3>(a, antithetic, s);
+        default: return launch_variant<4, 4>(a, antithetic, s);
         }
     }
     switch (rmode) {
     case 0: return launch_variant<8, 0>(a, antithetic, s);
     case 1: return launch_variant<8, 1>(a, antithetic, s);
     case 2: return launch_variant<8, 2>(a, antithetic, s);
-    default: return launch_variant<8, 3>(a, antithetic, s);
+    case 3: return launch_variant<8, 3>(a, antithetic, s);
+    default: return launch_variant<8, 4>(a, antithetic, s);
     }
 }
 
