@@ -9,6 +9,7 @@ Inputs are resident in HBM before the timed region starts. Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -49,6 +50,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", type=int, default=2, choices=sorted(wl.CONFIGS))
     ap.add_argument("--layers", type=int, default=None, help="limit the number of layers (debug)")
+    ap.add_argument("--K", type=int, default=None, help="override the replay window of the configuration")
+    ap.add_argument("--N", type=int, default=None, help="override the population of the configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--antithetic", action="store_true",
                     help="members come in +δ/-δ pairs sharing a seed (App. A.1); not the headline setting")
@@ -73,6 +76,12 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     cfg = wl.CONFIGS[args.config]
+    if args.K is not None or args.N is not None:
+        # the replay window is a cost knob (§4.6, App. E.2: cost linear in K); not the headline setting
+        cfg = dataclasses.replace(cfg, K=cfg.K if args.K is None else args.K, N=cfg.N if args.N is None else args.N)
+        if not (0 <= cfg.K <= 256 and 1 <= cfg.N <= 1024):
+            print("bench.py: --K must be in 0..256 and --N in 1..1024", file=sys.stderr)
+            sys.exit(2)
     n_layers = cfg.n_layers if args.layers is None else min(args.layers, cfg.n_layers)
     big = cfg.params > 100_000_000
     steps = args.steps if args.steps is not None else (2 if big else 20)

@@ -1,5 +1,5 @@
 """GPU parity for the Full-Residual variant (paper Alg. 1, Eq. 6-8 with a stored residual) and the
-on-device fidelity check of §4.4: replayed residual (Alg. 2) against the stored one."""
+on-device fidelity check of §4.5: replayed residual (Alg. 2) against the stored one."""
 import numpy as np
 import pytest
 
