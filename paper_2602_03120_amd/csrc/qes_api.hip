@@ -309,15 +309,25 @@ static int gemm_common(const qes_tensor *w, const uint64_t *seeds, const uint8_t
     rc = acquire_slot((size_t)N * sizeof(qes::Entry), &slot);
     if (rc != QES_OK) return rc;
     qes::Entry *ent = (qes::Entry *)slot->host;
-    for (int32_t i = 0; i < N; ++i) {
-        // antithetic pairs: members 2j and 2j+1 share seed j; the odd member uses -δ (mode 2)
-        const uint64_t sd = antithetic ? seeds[i / 2] : seeds[i];
-        const uint32_t mode = (perturb_mask != nullptr && perturb_mask[i] == 0) ? 0u : ((antithetic && (i & 1)) ? 2u : 1u);
-        ent[i] = qes::Entry{(uint32_t)sd, (uint32_t)(sd >> 32), mode, 0u};
+    // antithetic pairs share one draw inside a workgroup when both members' accumulators fit
+    // and two workgroups still share a CU; longer token counts regenerate the draw per member (mode 2 = -δ)
+    const bool paired = antithetic && qes::gemm_pairs_supported(T);
+    const int32_t records = paired ? N / 2 : N;
+    auto on = [&](int32_t i) { return !(perturb_mask != nullptr && perturb_mask[i] == 0); };
+    for (int32_t i = 0; i < records; ++i) {
+        if (paired) {
+            const uint64_t sd = seeds[i];
+            const uint32_t mode = (on(2 * i) ? 1u : 0u) | (on(2 * i + 1) ? 2u : 0u);
+            ent[i] = qes::Entry{(uint32_t)sd, (uint32_t)(sd >> 32), mode, 0u};
+        } else {
+            const uint64_t sd = antithetic ? seeds[i / 2] : seeds[i];
+            const uint32_t mode = !on(i) ? 0u : ((antithetic && (i & 1)) ? 2u : 1u);
+            ent[i] = qes::Entry{(uint32_t)sd, (uint32_t)(sd >> 32), mode, 0u};
+        }
     }
-    QES_HIP(hipMemcpyAsync(slot->dev, slot->host, (size_t)N * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
+    QES_HIP(hipMemcpyAsync(slot->dev, slot->host, (size_t)records * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
     a.entries = (const qes::Entry *)slot->dev;
-    hipError_t e = qes::launch_gemm(a, w->bits, act_mode, s);
+    hipError_t e = qes::launch_gemm(a, w->bits, act_mode, paired, s);
     hipError_t e2 = hipEventRecord(slot->ev, s);
     if (e2 == hipSuccess) slot->in_flight = true;
     else if (e == hipSuccess) e = e2;

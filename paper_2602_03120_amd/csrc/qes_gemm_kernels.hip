@@ -8,15 +8,19 @@
 // exactly once and that the noise arithmetic is spread evenly over all waves, with the MFMAs, the
 // LDS traffic and the global loads hidden underneath it.
 //
-// Decomposition. A workgroup owns one member, RG groups of 16 output rows and ALL tokens of that
-// member (TM per pass). Each row group is served by kTS = 4 waves. Per k-substep (32 k for bf16,
-// 64 k for int8 operands) the MFMA B fragment of a row group is 4 dwords per lane; wave ts
-// regenerates dword ts of it (one or two Philox pairs: draw, gate against the base integers, pack
-// as exact small-integer bf16 or int8), publishes it through LDS, and after the workgroup barrier
-// every wave of the group reads the whole fragment back (one b128) and runs the MFMAs of its own
-// share of the token tiles. So the noise work per wave is a quarter of a fragment whatever the
-// token count, the accumulators per wave are a quarter of the token tiles (high occupancy), and
-// short token counts still use all four waves for noise.
+// Decomposition. A workgroup (8 waves) owns one member, 4 groups of 16 output rows and ALL tokens
+// of that member (TM per pass). Per k-substep (32 k for bf16, 64 k for int8 operands) the MFMA B
+// fragment of a row group is 4 dwords per lane; each wave regenerates one half of one row group's
+// fragment (two or four Philox pairs per lane: draw, gate against the base integers, pack as exact
+// small-integer bf16 or int8), publishes it through LDS, and after the workgroup barrier wave
+// (wm, wr) reads the fragments of row groups 2 wr and 2 wr + 1 back (one b128 each) and runs the
+// MFMAs of the token tiles m = wm (mod 4). So the noise work per wave is an eighth of the
+// workgroup's whatever the token count, and short token counts still use all waves for noise.
+//
+// Antithetic pairs (PAIRED). Members 2j and 2j+1 use +δ and -δ of one draw, so a workgroup owns the
+// pair: every draw is generated once, gated twice (W+δ for the even member, W-δ for the odd one),
+// published as two fragments, and each member's token tiles meet their own fragment. Half the
+// noise work per member; accumulators, activation tiles and MFMAs are per member as before.
 //
 // Pipelining. B fragments are double-buffered in LDS: the dword for substep s+1 is generated while
 // the MFMAs of substep s run. The activation tile of substep s+1 goes straight from global memory
@@ -93,6 +97,22 @@ __device__ __forceinline__ bool block_to_work(uint32_t n_tiles, uint32_t n_membe
     return true;
 }
 
+// One pair of elements for both members of an antithetic pair: one draw; the even member gates
+// W + δ, the odd member W - δ (Eq. 4 each). keep_even / keep_odd are all-ones or zero: a member
+// whose perturbation is switched off gates W + 0 = W.
+__device__ __forceinline__ void perturb_pair_both(const int32_t (&w)[2], int32_t (&even)[2], int32_t (&odd)[2], uint32_t k0,
+                                                  uint32_t k1, uint32_t tensor_id, uint32_t pair, float sigma, int32_t qmin,
+                                                  uint32_t qspan, int32_t keep_even, int32_t keep_odd)
+{
+    int32_t d[2];
+    delta_pair(k0, k1, tensor_id, pair, sigma, d[0], d[1]);
+#pragma unroll
+    for (int l = 0; l < 2; ++l) {
+        even[l] = gate(w[l], d[l] & keep_even, qmin, qspan);
+        odd[l] = gate(w[l], (-d[l]) & keep_odd, qmin, qspan);
+    }
+}
+
 // One pair: draw, gate (Eq. 4) in place. SIGN = -1 is the mirrored member of an antithetic pair.
 template <int SIGN>
 __device__ __forceinline__ void perturb_pair(int32_t &w0, int32_t &w1, uint32_t k0, uint32_t k1, uint32_t tensor_id,
@@ -121,8 +141,9 @@ __device__ __forceinline__ uint32_t pack_i8x4(int32_t a, int32_t b, int32_t c, i
 // with row bits 2..3 so that the 16 rows one b128 fragment read touches spread over all banks.
 __device__ __forceinline__ int swizzle(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
 
-template <int MODE, int TM>
+template <int MODE, int TM, bool PAIRED>
 struct Gemm {
+    static constexpr int kP = PAIRED ? 2 : 1;                  // members per workgroup
     static constexpr bool kI8 = (MODE == kI8W8);
     static constexpr int kSubK = kI8 ? 64 : 32;                // k extent of one substep
     static constexpr int kElemBytes = kI8 ? 1 : 2;             // activation element
@@ -142,16 +163,17 @@ struct Gemm {
     bool tail;                    // int8 only: in_features % 64 == 32, the last substep is half empty
     const uint16_t *scales[kWR];  // scale rows of this lane's two MFMA row groups
     const uint16_t *job_scales;   // scale row of this lane's noise job
-    const char *xg;               // this member's activations
+    const char *xg[kP];           // activations of this workgroup's member(s)
+    int32_t keep[2];              // PAIRED: all-ones / zero per member: perturbation on / off
     const char *wrow_lane;        // this lane's packed base integers of substep 0 (noise job)
     uint32_t pair0;               // pair index of this lane's half fragment of substep 0
     uint32_t a_off;               // LDS offset of this lane's A fragment of token tile wm
     uint32_t frag_rd[kWR];        // LDS offsets of this lane's two B fragments inside a fragment buffer
     uint32_t frag_wr;             // LDS offset of this lane's half fragment (noise job)
-    char *bfrag;                  // 2 * kFragBytes
+    char *bfrag;                  // 2 buffers x kP members x kFragBytes
     // per pass
     uint32_t tile_off[kMyInstr];  // global offset of this lane's 16-byte chunk of substep 0, per instruction
-    Acc acc[kMy][kWR];
+    Acc acc[kP][kMy][kWR];
     float s_cur[kWR];
     bool job_zero;
     int subs_per_group, subs_to_group_end;
@@ -178,19 +200,23 @@ struct Gemm {
 
     __device__ __forceinline__ void issue_tile(int s, char *buf) const
     {
-        const char *sbase = xg + (size_t)s * (kSubK * kElemBytes);   // wave-uniform
 #pragma unroll
-        for (int i = 0; i < kMyInstr; ++i) {
-            const int j = i * kWaves + wave;
-            if (kInstr % kWaves != 0 && j >= kInstr) break;
-            uint32_t off = tile_off[i];
-            if (kI8 && tail && s == n_sub - 1) {
-                // chunks 2 and 3 of the half-empty last substep lie past the row: read chunk 0
-                // instead (in bounds); the fragments they meet are zero
-                const int ch = swizzle(j * 16 + (lane >> 2), lane & 3);
-                if (ch >= 2) off -= ch * 16;
+        for (int h = 0; h < kP; ++h) {
+            const char *sbase = xg[h] + (size_t)s * (kSubK * kElemBytes);   // wave-uniform
+#pragma unroll
+            for (int i = 0; i < kMyInstr; ++i) {
+                const int j = i * kWaves + wave;
+                if (kInstr % kWaves != 0 && j >= kInstr) break;
+                uint32_t off = tile_off[i];
+                if (kI8 && tail && s == n_sub - 1) {
+                    // chunks 2 and 3 of the half-empty last substep lie past the row: read chunk 0
+                    // instead (in bounds); the fragments they meet are zero
+                    const int ch = swizzle(j * 16 + (lane >> 2), lane & 3);
+                    if (ch >= 2) off -= ch * 16;
+                }
+                __builtin_amdgcn_global_load_lds((gbl_void *)(sbase + off), (lds_void *)(buf + h * kTileBytes + j * 1024), 16, 0,
+                                                 0);
             }
-            __builtin_amdgcn_global_load_lds((gbl_void *)(sbase + off), (lds_void *)(buf + j * 1024), 16, 0, 0);
         }
     }
 
@@ -206,8 +232,18 @@ struct Gemm {
     }
 
     // this wave's half of a B fragment of substep s: draw, gate (Eq. 4), pack as exact small integers
+    struct Halves {
+        uint2 d[kP];
+    };
+
+    __device__ __forceinline__ uint2 pack_half(const int32_t (&w)[H]) const
+    {
+        if (kI8) return make_uint2(pack_i8x4(w[0], w[1], w[2], w[3]), pack_i8x4(w[H - 4], w[H - 3], w[H - 2], w[H - 1]));
+        return make_uint2(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]));
+    }
+
     template <int PERTURB>
-    __device__ __forceinline__ uint2 make_half(int s, uint2 raw, bool zero) const
+    __device__ __forceinline__ Halves make_half(int s, uint2 raw, bool zero) const
     {
         int32_t w[H];
         if (MODE == kBf16W4) {
@@ -223,18 +259,44 @@ struct Gemm {
                 w[4 + j] = ((int32_t)(raw.y << (24 - 8 * j))) >> 24;
             }
         }
-        if (PERTURB != 0) {
-            const uint32_t pair = pair0 + (uint32_t)s * (kSubK / 2);
+        Halves out;
+        const uint32_t pair = pair0 + (uint32_t)s * (kSubK / 2);
+        if constexpr (PAIRED) {
+            int32_t even[H], odd[H];
 #pragma unroll
-            for (int p = 0; p < H / 2; ++p)
-                perturb_pair<PERTURB>(w[2 * p], w[2 * p + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair + p, a.sigma, a.qmin,
-                             a.qspan);
+            for (int p = 0; p < H / 2; ++p) {
+                const int32_t wp[2] = {w[2 * p], w[2 * p + 1]};
+                int32_t e2[2] = {wp[0], wp[1]}, o2[2] = {wp[0], wp[1]};
+                if (PERTURB != 0)
+                    perturb_pair_both(wp, e2, o2, en.seed_lo, en.seed_hi, a.tensor_id, pair + p, a.sigma, a.qmin, a.qspan,
+                                      keep[0], keep[1]);
+                even[2 * p] = e2[0];
+                even[2 * p + 1] = e2[1];
+                odd[2 * p] = o2[0];
+                odd[2 * p + 1] = o2[1];
+            }
+            out.d[0] = pack_half(even);
+            out.d[kP - 1] = pack_half(odd);
+        } else {
+            if (PERTURB != 0) {
+#pragma unroll
+                for (int p = 0; p < H / 2; ++p)
+                    perturb_pair<PERTURB>(w[2 * p], w[2 * p + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair + p, a.sigma, a.qmin,
+                                          a.qspan);
+            }
+            out.d[0] = pack_half(w);
         }
-        uint2 d;
-        if (kI8) d = make_uint2(pack_i8x4(w[0], w[1], w[2], w[3]), pack_i8x4(w[H - 4], w[H - 3], w[H - 2], w[H - 1]));
-        else d = make_uint2(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]));
-        if (zero || (kI8 && tail && s == n_sub - 1 && kc >= 2)) d = make_uint2(0u, 0u);
-        return d;
+        if (zero || (kI8 && tail && s == n_sub - 1 && kc >= 2)) {
+#pragma unroll
+            for (int h = 0; h < kP; ++h) out.d[h] = make_uint2(0u, 0u);
+        }
+        return out;
+    }
+
+    __device__ __forceinline__ void publish(int buffer, const Halves &hv)
+    {
+#pragma unroll
+        for (int h = 0; h < kP; ++h) *(uint2 *)(bfrag + (buffer * kP + h) * kFragBytes + frag_wr) = hv.d[h];
     }
 
     // scales of group g+1, requested when group g opens so that nothing waits for them
@@ -258,16 +320,21 @@ struct Gemm {
         const uint2 raw = raw_next;                   // for substep s+1, fetched during substep s-1
         if (s + 2 < n_sub) raw_next = load_raw(s + 2);
 
-        Frag b[kWR];
+        Frag b[kP][kWR];
 #pragma unroll
-        for (int r = 0; r < kWR; ++r) b[r].v = *(const uint4 *)(bfrag + PAR * kFragBytes + frag_rd[r]);
+        for (int h = 0; h < kP; ++h)
+#pragma unroll
+            for (int r = 0; r < kWR; ++r) b[h][r].v = *(const uint4 *)(bfrag + (PAR * kP + h) * kFragBytes + frag_rd[r]);
         constexpr int kBatch = kMy < 4 ? kMy : 4;   // A fragments in flight at a time
+        constexpr int kSteps = kP * kMy;            // (member, token tile) items of this wave, member-major
         Frag af[kBatch];
-        auto read_batch = [&](int i0) {
+        auto read_batch = [&](int q0) {
 #pragma unroll
-            for (int i = 0; i < kBatch; ++i)
-                if (kMT % kWM == 0 || wm + (i0 + i) * kWM < kMT)
-                    af[i].v = *(const uint4 *)(xbuf + a_off + (i0 + i) * kWM * 16 * kRowBytes);
+            for (int q = 0; q < kBatch; ++q) {
+                const int h = (q0 + q) / kMy, i = (q0 + q) % kMy;
+                if (kMT % kWM == 0 || wm + i * kWM < kMT)
+                    af[q].v = *(const uint4 *)(xbuf + h * kTileBytes + a_off + i * kWM * 16 * kRowBytes);
+            }
         };
         read_batch(0);
 
@@ -282,21 +349,22 @@ struct Gemm {
                     job_zero = ((job_scale_next & 0x7FFFu) == 0);
                 }
             }
-            *(uint2 *)(bfrag + (1 - PAR) * kFragBytes + frag_wr) = make_half<PERTURB>(s + 1, raw, job_zero);
+            publish(1 - PAR, make_half<PERTURB>(s + 1, raw, job_zero));
         }
 
 #pragma unroll
-        for (int i0 = 0; i0 < kMy; i0 += kBatch) {
-            if (i0 > 0) read_batch(i0);
+        for (int q0 = 0; q0 < kSteps; q0 += kBatch) {
+            if (q0 > 0) read_batch(q0);
 #pragma unroll
-            for (int i = 0; i < kBatch; ++i) {
-                if (kMT % kWM != 0 && wm + (i0 + i) * kWM >= kMT) continue;
+            for (int q = 0; q < kBatch; ++q) {
+                const int h = (q0 + q) / kMy, i = (q0 + q) % kMy;
+                if (kMT % kWM != 0 && wm + i * kWM >= kMT) continue;
 #pragma unroll
                 for (int r = 0; r < kWR; ++r) {
                     if constexpr (kI8)
-                        acc[i0 + i][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[i].i8, b[r].i8, acc[i0 + i][r], 0, 0, 0);
+                        acc[h][i][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[q].i8, b[h][r].i8, acc[h][i][r], 0, 0, 0);
                     else
-                        acc[i0 + i][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i].bf, b[r].bf, acc[i0 + i][r], 0, 0, 0);
+                        acc[h][i][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[q].bf, b[h][r].bf, acc[h][i][r], 0, 0, 0);
                 }
             }
         }
@@ -311,7 +379,9 @@ struct Gemm {
                         const float ratio = s_cur[r] / s_new;
                         s_cur[r] = s_new;
 #pragma unroll
-                        for (int i = 0; i < kMy; ++i) acc[i][r] *= ratio;
+                        for (int h = 0; h < kP; ++h)
+#pragma unroll
+                            for (int i = 0; i < kMy; ++i) acc[h][i][r] *= ratio;
                     }
                 }
                 prefetch_scales(group);
@@ -324,13 +394,15 @@ struct Gemm {
     }
 
     template <int PERTURB>
-    __device__ __forceinline__ void pass(int t0, int n0, char *x0, char *x1, uint16_t *yg, const float *xs,
-                                         const float (&s_row)[kWR])
+    __device__ __forceinline__ void pass(int t0, int n0, char *x0, char *x1, uint16_t *const (&yg)[kP],
+                                         const float *const (&xs)[kP], const float (&s_row)[kWR])
     {
 #pragma unroll
-        for (int i = 0; i < kMy; ++i)
+        for (int h = 0; h < kP; ++h)
 #pragma unroll
-            for (int r = 0; r < kWR; ++r) acc[i][r] = Acc{0, 0, 0, 0};
+            for (int i = 0; i < kMy; ++i)
+#pragma unroll
+                for (int r = 0; r < kWR; ++r) acc[h][i][r] = Acc{0, 0, 0, 0};
         group = 0;
         subs_to_group_end = subs_per_group;
         job_zero = false;
@@ -348,7 +420,7 @@ struct Gemm {
         __syncthreads();   // the previous pass has finished reading LDS
         issue_tile(0, x0);
         raw_next = n_sub > 1 ? load_raw(1) : make_uint2(0u, 0u);
-        *(uint2 *)(bfrag + frag_wr) = make_half<PERTURB>(0, load_raw(0), job_zero);
+        publish(0, make_half<PERTURB>(0, load_raw(0), job_zero));
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
 
@@ -358,41 +430,46 @@ struct Gemm {
         }
 
 #pragma unroll
-        for (int r = 0; r < kWR; ++r) {
-            const int n = n0 + (wr * kWR + r) * 16 + ln;
-            if (n >= a.out_features) continue;
+        for (int h = 0; h < kP; ++h)
 #pragma unroll
-            for (int i = 0; i < kMy; ++i) {
-                const int m = wm + i * kWM;
-                if (kMT % kWM != 0 && m >= kMT) continue;
+            for (int r = 0; r < kWR; ++r) {
+                const int n = n0 + (wr * kWR + r) * 16 + ln;
+                if (n >= a.out_features) continue;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int t = t0 + m * 16 + kc * 4 + j;
-                    if (t < a.T) {
-                        float v;
-                        if constexpr (kI8) v = ((float)acc[i][r][j] * xs[t]) * s_row[r];
-                        else v = acc[i][r][j] * s_cur[r];
-                        yg[(size_t)t * a.out_features + n] = f32_to_bf16_rne(v);
+                for (int i = 0; i < kMy; ++i) {
+                    const int m = wm + i * kWM;
+                    if (kMT % kWM != 0 && m >= kMT) continue;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int t = t0 + m * 16 + kc * 4 + j;
+                        if (t < a.T) {
+                            float v;
+                            if constexpr (kI8) v = ((float)acc[h][i][r][j] * xs[h][t]) * s_row[r];
+                            else v = acc[h][i][r][j] * s_cur[r];
+                            yg[h][(size_t)t * a.out_features + n] = f32_to_bf16_rne(v);
+                        }
                     }
                 }
             }
-        }
     }
 };
 
-template <int MODE, int TM>
-__global__ __launch_bounds__(kThreads, (TM >= 512 ? 4 : 1)) void gemm_kernel(const GemmArgs a)
+template <int MODE, int TM, bool PAIRED>
+// register budget: two workgroups per CU (4 waves per SIMD) also for the largest accumulator sets
+__global__ __launch_bounds__(kThreads, ((!PAIRED && TM >= 512) || (PAIRED && TM == 128) ? 4 : 1)) void gemm_kernel(const GemmArgs a)
 {
-    using G = Gemm<MODE, TM>;
+    using G = Gemm<MODE, TM, PAIRED>;
+    constexpr int kP = G::kP;
     // separate arrays, not halves of one: reads of one tile buffer must not wait for the
     // asynchronous loads into the other, and the compiler tells them apart per LDS variable
-    __shared__ __attribute__((aligned(1024))) char x0[G::kTileBytes];
-    __shared__ __attribute__((aligned(1024))) char x1[G::kTileBytes];
-    __shared__ __attribute__((aligned(16))) char bfrag[2 * kFragBytes];
+    __shared__ __attribute__((aligned(1024))) char x0[kP * G::kTileBytes];
+    __shared__ __attribute__((aligned(1024))) char x1[kP * G::kTileBytes];
+    __shared__ __attribute__((aligned(16))) char bfrag[2 * kP * kFragBytes];
 
+    // work item: a member, or an antithetic pair of members (PAIRED; a.entries then holds one record per pair)
     uint32_t member, tile;
     const uint32_t n_tiles = (a.out_features + kTileN - 1) / kTileN;
-    if (!block_to_work(n_tiles, (uint32_t)a.N, member, tile)) return;
+    if (!block_to_work(n_tiles, (uint32_t)a.N / kP, member, tile)) return;
 
     G g{a};
     g.lane = threadIdx.x & 63;
@@ -419,7 +496,15 @@ __global__ __launch_bounds__(kThreads, (TM >= 512 ? 4 : 1)) void gemm_kernel(con
         s_row[r] = G::kI8 ? f16_bits_to_f32(((const uint16_t *)a.scales)[n]) : 1.0f;
         g.frag_rd[r] = (g.wr * kWR + r) * 1024 + g.lane * 16;
     }
-    g.xg = (const char *)a.x + (size_t)member * a.T * a.in_features * G::kElemBytes;
+    uint16_t *yg[kP];
+    const float *xs[kP];
+#pragma unroll
+    for (int h = 0; h < kP; ++h) {
+        const size_t m = (size_t)member * kP + h;
+        g.xg[h] = (const char *)a.x + m * a.T * a.in_features * G::kElemBytes;
+        yg[h] = (uint16_t *)a.y + m * a.T * a.out_features;
+        xs[h] = G::kI8 ? a.x_scale + m * a.T : nullptr;
+    }
     // noise job: half `jhalf` of row group jrg: elements k0 .. k0+H-1, k0 = s*kSubK + kc*(kSubK/4) + jhalf*H
     const int jn = clamp_row(n0 + g.jrg * 16 + g.ln);
     const int k0 = g.kc * (G::kSubK / 4) + g.jhalf * G::H;
@@ -430,14 +515,21 @@ __global__ __launch_bounds__(kThreads, (TM >= 512 ? 4 : 1)) void gemm_kernel(con
     g.frag_wr = g.jrg * 1024 + g.lane * 16 + g.jhalf * 8;
     g.a_off = (g.wm * 16 + g.ln) * kRowBytes + swizzle(g.ln, g.kc) * 16;
     g.bfrag = bfrag;
-    uint16_t *yg = (uint16_t *)a.y + (size_t)member * a.T * a.out_features;
-    const float *xs = G::kI8 ? a.x_scale + (size_t)member * a.T : nullptr;
-    const uint32_t mode = (a.sigma != 0.0f) ? g.en.fit_bits : 0u;   // 0 base weights, 1 +δ, 2 -δ (antithetic mirror)
+    // per member: 0 base weights, 1 +δ, 2 -δ (antithetic mirror); per pair: bit 0 = even member
+    // perturbed, bit 1 = odd member perturbed
+    const uint32_t mode = (a.sigma != 0.0f) ? g.en.fit_bits : 0u;
+    g.keep[0] = (mode & 1u) ? -1 : 0;
+    g.keep[1] = (mode & 2u) ? -1 : 0;
 
     for (int t0 = 0; t0 < a.T; t0 += TM) {
-        if (mode == 1u) g.template pass<1>(t0, n0, x0, x1, yg, xs, s_row);
-        else if (mode == 2u) g.template pass<-1>(t0, n0, x0, x1, yg, xs, s_row);
-        else g.template pass<0>(t0, n0, x0, x1, yg, xs, s_row);
+        if constexpr (PAIRED) {
+            if (mode != 0u) g.template pass<1>(t0, n0, x0, x1, yg, xs, s_row);
+            else g.template pass<0>(t0, n0, x0, x1, yg, xs, s_row);
+        } else {
+            if (mode == 1u) g.template pass<1>(t0, n0, x0, x1, yg, xs, s_row);
+            else if (mode == 2u) g.template pass<-1>(t0, n0, x0, x1, yg, xs, s_row);
+            else g.template pass<0>(t0, n0, x0, x1, yg, xs, s_row);
+        }
     }
 }
 
@@ -465,24 +557,24 @@ __global__ __launch_bounds__(256) void quantize_kernel(const uint16_t *__restric
     }
 }
 
-template <int MODE, int TM>
+template <int MODE, int TM, bool PAIRED>
 void launch_one(const GemmArgs &a, hipStream_t s)
 {
     const uint32_t n_tiles = (a.out_features + kTileN - 1) / kTileN;
-    const uint32_t total = n_tiles * (uint32_t)a.N;
+    const uint32_t total = n_tiles * ((uint32_t)a.N / (PAIRED ? 2u : 1u));
     const unsigned blocks = ((total + 7u) / 8u) * 8u;
-    gemm_kernel<MODE, TM><<<blocks, kThreads, 0, s>>>(a);
+    gemm_kernel<MODE, TM, PAIRED><<<blocks, kThreads, 0, s>>>(a);
 }
 
-template <int MODE>
+template <int MODE, bool PAIRED>
 hipError_t launch_mode(const GemmArgs &a, hipStream_t s)
 {
-    if (a.T <= 16) launch_one<MODE, 16>(a, s);
-    else if (a.T <= 32) launch_one<MODE, 32>(a, s);
-    else if (a.T <= 64) launch_one<MODE, 64>(a, s);
-    else if (a.T <= 128) launch_one<MODE, 128>(a, s);
-    else if (a.T <= 256) launch_one<MODE, 256>(a, s);
-    else launch_one<MODE, 512>(a, s);
+    if (a.T <= 16) launch_one<MODE, 16, PAIRED>(a, s);
+    else if (a.T <= 32) launch_one<MODE, 32, PAIRED>(a, s);
+    else if (a.T <= 64) launch_one<MODE, 64, PAIRED>(a, s);
+    else if (a.T <= 128 || PAIRED) launch_one<MODE, 128, PAIRED>(a, s);
+    else if (a.T <= 256) launch_one<MODE, 256, false>(a, s);
+    else launch_one<MODE, 512, false>(a, s);
     return hipGetLastError();
 }
 
@@ -497,10 +589,21 @@ hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_
     return hipGetLastError();
 }
 
-hipError_t launch_gemm(const GemmArgs &a, int bits, int act_mode, hipStream_t s)
+// A pair's workgroup holds the accumulators of both members. Up to 128 tokens per member that
+// leaves room for two workgroups per CU and the shared draw wins (1.4-1.6x per launch); at 256
+// tokens the 64 accumulator registers per lane take the whole CU and the gain is lost, so longer
+// token counts regenerate the draw per member.
+bool gemm_pairs_supported(int32_t T) { return T <= 128; }
+
+hipError_t launch_gemm(const GemmArgs &a, int bits, int act_mode, bool paired, hipStream_t s)
 {
-    if (act_mode == 1) return launch_mode<kI8W8>(a, s);
-    return bits == 4 ? launch_mode<kBf16W4>(a, s) : launch_mode<kBf16W8>(a, s);
+    if (paired) {
+        if (!gemm_pairs_supported(a.T) || (a.N & 1)) return hipErrorInvalidValue;
+        if (act_mode == 1) return launch_mode<kI8W8, true>(a, s);
+        return bits == 4 ? launch_mode<kBf16W4, true>(a, s) : launch_mode<kBf16W8, true>(a, s);
+    }
+    if (act_mode == 1) return launch_mode<kI8W8, false>(a, s);
+    return bits == 4 ? launch_mode<kBf16W4, false>(a, s) : launch_mode<kBf16W8, false>(a, s);
 }
 
 }  // namespace qes

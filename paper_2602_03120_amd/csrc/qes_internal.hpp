@@ -31,7 +31,7 @@ struct UpdateArgs {
 struct GemmArgs {
     const void *qweight;
     const void *scales;          // fp16
-    const Entry *entries;        // [N]: seed + perturb flag
+    const Entry *entries;        // [N]: seed + perturb flag ([N/2] for the paired launch)
     const void *x;               // bf16 [N,T,in] (act_mode 0) or int8 [N,T,in] (act_mode 1)
     const float *x_scale;        // act_mode 1: [N,T]
     void *y;                     // bf16 [N,T,out]
@@ -61,6 +61,9 @@ hipError_t launch_update(const UpdateArgs &a, int bits, int rmode, bool antithet
 hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_scale, int64_t rows,
                                        int32_t in_features, hipStream_t s);
 // returns hipErrorInvalidValue when no kernel covers the request
-hipError_t launch_gemm(const GemmArgs &a, int bits, int act_mode, hipStream_t s);
+// paired: a.entries holds one record per antithetic pair (fit_bits bit 0 / bit 1: even / odd member
+// perturbed) and one workgroup evaluates both members from one draw; needs gemm_pairs_supported(T)
+bool gemm_pairs_supported(int32_t T);
+hipError_t launch_gemm(const GemmArgs &a, int bits, int act_mode, bool paired, hipStream_t s);
 
 }  // namespace qes

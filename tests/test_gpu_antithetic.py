@@ -45,9 +45,17 @@ def test_update_and_replay(env, bits, out_f, in_f, K, N, sigma):
     assert (stats.cpu().numpy().view(np.uint64) == ref_stats).all() and ref_stats[0] > 0
 
 
-@pytest.mark.parametrize("bits,group,out_f,in_f,N,T,act", [(4, 128, 200, 384, 4, 64, 0), (4, 32, 64, 256, 8, 16, 0),
-                                                          (8, 0, 96, 224, 6, 33, 0), (8, 0, 128, 256, 2, 300, 1)])
-def test_gemm(env, bits, group, out_f, in_f, N, T, act):
+# up to 128 tokens per member one workgroup serves both members of a pair from one draw; longer
+# token counts regenerate the draw per member: both paths, every tile height of the shared one
+@pytest.mark.parametrize("bits,group,out_f,in_f,N,T,act,off", [
+    (4, 128, 200, 384, 4, 64, 0, (3,)), (4, 32, 64, 256, 8, 16, 0, (7,)), (8, 0, 96, 224, 6, 33, 0, (5,)),
+    (8, 0, 128, 256, 2, 300, 1, (1,)),          # per-member path, int8 activations
+    (4, 128, 200, 384, 4, 128, 0, (0,)),        # shared draw, tallest tile; the +δ member of pair 0 unperturbed
+    (8, 0, 128, 224, 4, 100, 1, (2, 3)),        # shared draw, int8 activations, ragged tokens and k; pair 1 unperturbed
+    (4, 64, 96, 512, 6, 130, 0, ()),            # just past the shared-draw limit
+    (8, 0, 80, 128, 2, 7, 0, (0, 1)),           # a single pair, both members unperturbed
+])
+def test_gemm(env, bits, group, out_f, in_f, N, T, act, off):
     torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
     qw, sc, qmin, qmax = wl.random_tensor(out_f + T, out_f, in_f, bits, group)
     ot = oracle.Tensor(qw, sc, out_f, in_f, bits, group, qmin, qmax, 44)
@@ -55,7 +63,7 @@ def test_gemm(env, bits, group, out_f, in_f, N, T, act):
     x = wl.f32_to_bf16_bits(rng.standard_normal((N, T, in_f)).astype(np.float32))
     pair_seeds = rng.integers(0, 2 ** 63, size=N // 2, dtype=np.uint64)
     mask = np.ones(N, dtype=np.uint8)
-    mask[-1] = 0                                            # the last mirrored member runs unperturbed
+    mask[list(off)] = 0                                     # these members run on the base weights
     dt = u.device_tensor(ot)
     y = torch.empty((N, T, out_f), dtype=torch.bfloat16, device=u.DEV)
     nbytes = qes.gemm_workspace_bytes(dt, N, T, act)
@@ -69,9 +77,10 @@ def test_gemm(env, bits, group, out_f, in_f, N, T, act):
     else:
         ok, worst = u.bf16_close(got, ref)
         assert ok, worst
-        # the mirrored members really differ from the +δ evaluation of the same seed
-        plus = oracle.perturbed_qgemm(ot, np.repeat(pair_seeds, 2), 1.0, x, perturb_mask=mask)
-        assert not u.bf16_close(got[1:2], plus[1:2])[0]
+        if 1 not in off:
+            # the mirrored members really differ from the +δ evaluation of the same seed
+            plus = oracle.perturbed_qgemm(ot, np.repeat(pair_seeds, 2), 1.0, x, perturb_mask=mask)
+            assert not u.bf16_close(got[1:2], plus[1:2])[0]
 
 
 def test_odd_population_is_refused(env):
