@@ -10,6 +10,8 @@
 //
 // Arithmetic order is part of the definition (bit-exact integer results):
 //   g = fma(F_i, δ_i, g) for i = 0..N-1;  u = fma(c, g, γ*e);  Δ = rne(u);  e = u - Δ_gated.
+#include <type_traits>
+
 #include "qes_internal.hpp"
 #include "qes_noise.hpp"
 
@@ -99,9 +101,8 @@ struct Raw {
 // round-to-nearest-even after saturating at the largest finite half). 4: the stateless baseline of
 // §5, W <- W + Q(c g) with stochastic rounding Q (no residual; rounding uniforms from the Philox
 // stream keyed by the step's rounding seed, stream tag 1).
-// A thread owns PPT pairs and regenerates the noise of MI members at a time; PPT*MI = 4 independent
-// Philox/Box-Muller chains are in flight per thread whatever the split, and the sum of Eq. 5 still
-// runs in member order. Small PPT makes waves short, which evens out the last round of a launch.
+// A thread owns PPT pairs and regenerates the noise of MI members at a time: PPT*MI independent
+// Philox/Box-Muller chains in flight per thread, while the sum of Eq. 5 still runs in member order.
 template <int BITS, int PPT, int MI, int RMODE, bool CLAMP, bool ANTI>
 __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs a)
 {
@@ -148,22 +149,29 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs a)
             for (int j = 0; j < PPT; ++j)
                 delta_pair_f32<CLAMP>(en.seed_lo, en.seed_hi, a.tensor_id, pair0 + j, a.sigma, d[2 * j], d[2 * j + 1]);
         };
+        // M members at a time: M x PPT independent chains, then the fmas in member order
+        auto round = [&](auto m_tag, int32_t first) {
+            constexpr int M = decltype(m_tag)::value;
+            Entry en[M];                                  // wave-uniform: scalar loads
+            float d[M][2 * PPT];
+#pragma unroll
+            for (int m = 0; m < M; ++m) en[m] = gen[first + m];
+#pragma unroll
+            for (int m = 0; m < M; ++m) draw(en[m], d[m]);
+#pragma unroll
+            for (int m = 0; m < M; ++m) accumulate(en[m], d[m]);
+        };
         int32_t i = 0;
-        for (; i + MI <= a.N; i += MI) {
-            Entry en[MI];                                 // wave-uniform: scalar loads
-            float d[MI][2 * PPT];
-#pragma unroll
-            for (int m = 0; m < MI; ++m) en[m] = gen[i + m];
-#pragma unroll
-            for (int m = 0; m < MI; ++m) draw(en[m], d[m]);
-#pragma unroll
-            for (int m = 0; m < MI; ++m) accumulate(en[m], d[m]);
+        for (; i + MI <= a.N; i += MI) round(std::integral_constant<int, MI>{}, i);
+        // N % MI leftover members, still as wide as they allow
+        if constexpr (MI >= 4) {
+            if (i + 2 <= a.N) {
+                round(std::integral_constant<int, 2>{}, i);
+                i += 2;
+            }
         }
-        for (; i < a.N; ++i) {                            // N % MI leftover members
-            const Entry en = gen[i];
-            float d[2 * PPT];
-            draw(en, d);
-            accumulate(en, d);
+        if constexpr (MI >= 2) {
+            if (i < a.N) round(std::integral_constant<int, 1>{}, i);
         }
         const bool last = (RMODE != 1) && (tau == a.steps - 1);
         uint32_t round_word[2 * PPT];
@@ -230,56 +238,27 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs a)
     }
 }
 
-template <int BITS, int RMODE, bool CLAMP, bool ANTI>
-void launch_ppt(const UpdateArgs &a, int ppt, unsigned blocks, hipStream_t s)
-{
-    switch (ppt) {
-    case 4: update_kernel<BITS, 4, 1, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
-    case 2: update_kernel<BITS, 2, 2, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
-    default: update_kernel<BITS, 1, 4, RMODE, CLAMP, ANTI><<<blocks, kBlock, 0, s>>>(a); break;
-    }
-}
-
-// Relative duration of a launch of `waves` waves whose work is proportional to ppt, on 1024 SIMDs
-// holding 8 waves each: whole rounds run at full rate; the waves left over run at the rate a SIMD
-// reaches with that few waves (measured with the noise loop: 1 wave 49 %, 2 waves 73 %, 4 waves
-// 93 % of the 8-wave rate).
-double launch_cost(uint64_t n_pairs, int ppt)
-{
-    const double x = (double)((n_pairs / ppt + 63) / 64) / (1024.0 * 8.0);
-    const double full = (double)(uint64_t)x;
-    const double f = x - full;
-    double tail = 0.0;
-    if (f > 0.0) {
-        const double pts[5][2] = {{0.0, 0.255}, {0.125, 0.255}, {0.25, 0.34}, {0.5, 0.54}, {1.0, 1.0}};
-        for (int k = 0; k < 4; ++k)
-            if (f >= pts[k][0] && f <= pts[k + 1][0])
-                tail = pts[k][1] + (pts[k + 1][1] - pts[k][1]) * (f - pts[k][0]) / (pts[k + 1][0] - pts[k][0]);
-    }
-    return (full + tail) * ppt;
-}
+// One pair per thread, four members at a time. Measured on the tensor shapes of every
+// configuration against 2 x 2 and 4 x 1 (pairs x members) and against 5, 6 and 8 members at a time:
+// four chains per thread at 8 waves per SIMD already reach the noise ceiling, and the shortest
+// waves give the cheapest last round of a launch, so this split is never slower.
+constexpr int kPairsPerThread = 1;
+constexpr int kMembersAtATime = 4;
 
 template <int BITS, int RMODE>
 hipError_t launch_variant(const UpdateArgs &a, bool antithetic, hipStream_t s)
 {
-    // pairs per thread: the split with the shortest predicted launch (ties go to the wider thread)
-    int ppt = 1;
-    double best = launch_cost(a.n_pairs, 1);
-    for (int cand = 2; cand <= 4; cand *= 2) {
-        if (a.n_pairs % cand) break;
-        const double c = launch_cost(a.n_pairs, cand);
-        if (c <= best) { best = c; ppt = cand; }
-    }
-    const uint64_t threads = a.n_pairs / ppt;
+    const uint64_t threads = a.n_pairs / kPairsPerThread;
     const unsigned blocks = (unsigned)((threads + kBlock - 1) / kBlock);
     // |sigma*eps| <= 1.2 * 5.77 < 7: the 4-bit container clamp cannot fire and is compiled out
     const bool clamp = !(a.sigma <= 1.2f);
+    constexpr int P = kPairsPerThread, M = kMembersAtATime;
     if (clamp) {
-        if (antithetic) launch_ppt<BITS, RMODE, true, true>(a, ppt, blocks, s);
-        else launch_ppt<BITS, RMODE, true, false>(a, ppt, blocks, s);
+        if (antithetic) update_kernel<BITS, P, M, RMODE, true, true><<<blocks, kBlock, 0, s>>>(a);
+        else update_kernel<BITS, P, M, RMODE, true, false><<<blocks, kBlock, 0, s>>>(a);
     } else {
-        if (antithetic) launch_ppt<BITS, RMODE, false, true>(a, ppt, blocks, s);
-        else launch_ppt<BITS, RMODE, false, false>(a, ppt, blocks, s);
+        if (antithetic) update_kernel<BITS, P, M, RMODE, false, true><<<blocks, kBlock, 0, s>>>(a);
+        else update_kernel<BITS, P, M, RMODE, false, false><<<blocks, kBlock, 0, s>>>(a);
     }
     return hipGetLastError();
 }

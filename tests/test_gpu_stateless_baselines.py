@@ -19,7 +19,6 @@ def env(oracle):
     return dict(torch=torch, qes=qes, u=gpu_util, oracle=oracle)
 
 
-# shapes cover every split of the kernel's four noise chains (see test_gpu_update.py)
 @pytest.mark.parametrize("bits,out_f,in_f,N,steps,alpha", [(4, 256, 256, 8, 4, 1.5), (4, 7, 34, 5, 3, 3.0),
                                                            (8, 1024, 1024, 5, 2, 1.5), (4, 2048, 1024, 4, 2, 1.5),
                                                            (8, 2048, 2048, 2, 1, 1.5), (4, 64, 64, 30, 3, 40.0)])

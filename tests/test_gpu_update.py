@@ -41,19 +41,18 @@ def _run_update(env, ot, seeds, fit, K, sigma, alpha, gamma, rows=None):
     return got, ref_t, stats.cpu().numpy().view(np.uint64), ref_stats
 
 
-# shapes chosen to hit every split of a thread's four noise chains (pairs per thread x members at a
-# time: 1x4, 2x2, 4x1; the library picks it from the pair count), populations that are and are not a
-# multiple of the members taken at a time, several blocks and ragged tails
+# the kernel takes four members at a time: populations that are a multiple of four, leave one, two
+# or three members over, or are smaller than one round; several blocks and ragged tails
 @pytest.mark.parametrize("bits,out_f,in_f,K,N", [
-    (4, 256, 256, 4, 8),        # config 1 layer; 1x4
-    (4, 7, 34, 3, 5),           # tiny, odd pair count; 1x4 with one member left over
-    (4, 1024, 2050, 2, 3),      # 1 049 600 pairs: 4x1
-    (4, 2048, 1024, 1, 4),      # 1M pairs: 2x2
-    (4, 1024, 1024, 2, 4),      # 512K pairs: 1x4
-    (8, 129, 66, 3, 6),         # 1x4, two members left over
-    (8, 2048, 1024, 1, 3),      # 2x2, one member left over
-    (8, 1024, 1024, 2, 2),      # 1x4, fewer members than a round
-    (8, 2048, 2048, 1, 2),      # 2M pairs: 4x1, int8
+    (4, 256, 256, 4, 8),        # config 1 layer
+    (4, 7, 34, 3, 5),           # tiny, odd pair count; one member left over
+    (4, 1024, 2050, 2, 3),      # more than a million pairs, fewer members than a round
+    (4, 2048, 1024, 1, 4),
+    (4, 1024, 1024, 2, 7),      # three members left over
+    (8, 129, 66, 3, 6),         # two members left over
+    (8, 2048, 1024, 1, 3),
+    (8, 1024, 1024, 2, 2),
+    (8, 2048, 2048, 1, 2),      # 2M pairs, int8
     (4, 64, 128, 0, 8),         # no history: stateless deterministic rounding (Eq. 9)
     (8, 64, 128, 5, 1),         # population of one
 ])
