@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="limit the number of layers (debug)")
     ap.add_argument("--K", type=int, default=None, help="override the replay window of the configuration")
     ap.add_argument("--N", type=int, default=None, help="override the population of the configuration")
+    ap.add_argument("--per-tensor-update", action="store_true",
+                    help="one qes_update call per tensor instead of one qes_update_batch call per layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--antithetic", action="store_true",
                     help="members come in +δ/-δ pairs sharing a seed (App. A.1); not the headline setting")
@@ -123,6 +125,7 @@ def main():
     rewards = wl.make_rewards(cfg, cfg.K + total_steps)
     fits = np.stack([qes.normalize_fitness(r) for r in rewards])
 
+    layer_tensors = [[t for la, _, t in tensors if la == layer] for layer in range(n_layers)]
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
     gemm_events, upd_events = [], []
 
@@ -135,16 +138,27 @@ def main():
             qes.perturbed_qgemm(t, seeds[cfg.K + s], cfg.sigma, xs[spec.x_key], ys[spec.out_features],
                                 act_mode=cfg.act_mode, workspace=ws, antithetic=anti)
         g1.record()
-        # seeded update with a full replay window (steady state: K generations of history)
+        # seeded update with a full replay window (steady state: K generations of history): all
+        # linears of a layer share the generation's records and go in one call
         h0 = s
-        for layer, li, t in tensors:
-            u0, u1 = ev(), ev()
-            u0.record()
-            qes.update(t, seeds[cfg.K + s], fits[cfg.K + s], seeds[h0:h0 + cfg.K], fits[h0:h0 + cfg.K],
-                       cfg.sigma, cfg.alpha, cfg.gamma, stats=stats, antithetic=anti)
-            u1.record()
-            if timed:
-                upd_events.append((li, u0, u1))
+        if args.per_tensor_update:
+            for layer, li, t in tensors:
+                u0, u1 = ev(), ev()
+                u0.record()
+                qes.update(t, seeds[cfg.K + s], fits[cfg.K + s], seeds[h0:h0 + cfg.K], fits[h0:h0 + cfg.K],
+                           cfg.sigma, cfg.alpha, cfg.gamma, stats=stats, antithetic=anti)
+                u1.record()
+                if timed:
+                    upd_events.append((li, u0, u1))
+        else:
+            for layer in range(n_layers):
+                u0, u1 = ev(), ev()
+                u0.record()
+                qes.update_batch(layer_tensors[layer], seeds[cfg.K + s], fits[cfg.K + s], seeds[h0:h0 + cfg.K],
+                                 fits[h0:h0 + cfg.K], cfg.sigma, cfg.alpha, cfg.gamma, stats=stats, antithetic=anti)
+                u1.record()
+                if timed:
+                    upd_events.append((-1, u0, u1))
         if timed:
             gemm_events.append((g0, g1))
 
@@ -169,14 +183,24 @@ def main():
     upd_ms_by_li = {}
     for li, a, b in upd_events:
         upd_ms_by_li.setdefault(li, []).append(a.elapsed_time(b))
-    # dominant kernel: the update of the largest tensor shape (most launches x longest)
-    dom_li = max(range(len(cfg.linears)), key=lambda i: cfg.linears[i].out_features * cfg.linears[i].in_features)
-    dom = cfg.linears[dom_li]
-    dom_ms = float(np.mean(upd_ms_by_li[dom_li]))
-    dom_elems = dom.out_features * dom.in_features
+    # dominant kernel: the update. One launch = one layer's linears (qes_update_batch), or, with
+    # --per-tensor-update, the largest tensor shape (most launches x longest)
+    if args.per_tensor_update:
+        dom_li = max(range(len(cfg.linears)), key=lambda i: cfg.linears[i].out_features * cfg.linears[i].in_features)
+        dom = cfg.linears[dom_li]
+        dom_ms = float(np.mean(upd_ms_by_li[dom_li]))
+        dom_elems = dom.out_features * dom.in_features
+        dom_name = "update_kernel (qes_update, %s %dx%d)" % (dom.name, dom.out_features, dom.in_features)
+        traffic_key = (cfg.index, dom.name)
+        upd_ms_total = float(sum(np.mean(v) for v in upd_ms_by_li.values())) * n_layers
+    else:
+        dom_ms = float(np.mean(upd_ms_by_li[-1]))
+        dom_elems = sum(l.out_features * l.in_features for l in cfg.linears)
+        dom_name = "update_kernel (qes_update_batch, one layer: %s)" % "+".join(l.name for l in cfg.linears)
+        traffic_key = (cfg.index, "layer")
+        upd_ms_total = dom_ms * n_layers
     ops = dom_elems * update_ops_per_element(cfg.N // 2 if anti else cfg.N, cfg.K + 1)
     achieved_tops = ops / (dom_ms * 1e-3) / 1e12
-    upd_ms_total = float(sum(np.mean(v) for v in upd_ms_by_li.values())) * n_layers
     bytes_per_param = cfg.bits / 8.0 * 2.0          # packed W read + written
     upd_gbps = params * bytes_per_param / (upd_ms_total * 1e-3) / 1e9
     upd_draws = params * (cfg.K + 1) * (cfg.N // 2 if anti else cfg.N)
@@ -197,13 +221,14 @@ def main():
         "config": {"workload": "config %d: %s (%d layers of %s), N=%d, T=%d, K=%d, sigma=%g, alpha=%g, gamma=%g"
                    % (cfg.index, cfg.name, n_layers, "/".join(l.name for l in cfg.linears), cfg.N, cfg.T, cfg.K,
                       cfg.sigma, cfg.alpha, cfg.gamma),
-                   "parameters": params, "step": "perturbed qGEMM of every linear + update with full replay window",
+                   "parameters": params, "step": "perturbed qGEMM of every linear + update with full replay window (%s)"
+                   % ("one call per tensor" if args.per_tensor_update else "one call per layer"),
                    "antithetic_pairs": bool(anti)},
         "roofline": {
-            "kernel": "update_kernel (qes_update, %s %dx%d)" % (dom.name, dom.out_features, dom.in_features),
+            "kernel": dom_name,
             "bound": "alu", "achieved": achieved_tops, "peak": VALU_PEAK_TOPS, "unit": "Tlane-op/s",
             "frac": achieved_tops / VALU_PEAK_TOPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.index, dom.name)),
+            "traffic": None if anti else MEASURED_TRAFFIC_BYTES.get(traffic_key),
             "avg_launch_ms": dom_ms,
             "algorithmic_ops_per_launch": ops,
             "algorithmic_bytes_per_launch": dom_elems * cfg.bits / 8.0 * 2.0,

@@ -41,6 +41,7 @@ typedef enum {
 /* Limits of the small HOST arrays. */
 #define QES_MAX_POPULATION 1024 /* N */
 #define QES_MAX_HISTORY 256     /* hist_len */
+#define QES_MAX_BATCH 4096      /* tensors per qes_update_batch call */
 
 /*
  * One quantised linear weight (App. A.1; INT4 group-scaled and INT8 per-output-channel formats).
@@ -176,6 +177,27 @@ int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const
 int qes_replay_residual(const qes_tensor *w, const uint64_t *hist_seeds, const float *hist_fit,
                         int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
                         float *residual, void *stream);
+
+/*
+ * qes_update (Alg. 2 whole) applied to every tensor of a list: all linears of a model share the
+ * generation's seeds, fitnesses and history, so the records are staged once and the tensors are
+ * updated by one launch per weight width, which also spares the partly filled last round of
+ * workgroups that every single-tensor launch ends with. Results are those of n_tensors qes_update
+ * calls (each element's noise depends on its own tensor_id and index only).
+ *
+ *   tensors    HOST array [n_tensors] of descriptors; 1 <= n_tensors <= QES_MAX_BATCH; their qweight
+ *              buffers are DEVICE memory as for qes_update and must not overlap; `scales` is unused
+ *   stats      DEVICE uint64 [2] or NULL: counters summed over all tensors
+ * Other arguments as for qes_update / qes_update_antithetic.
+ */
+int qes_update_batch(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *seeds_t, const float *fit_t,
+                     const uint64_t *hist_seeds, const float *hist_fit, int32_t hist_len, int32_t N, float sigma,
+                     float alpha, float gamma, uint64_t *stats, void *stream);
+
+int qes_update_batch_antithetic(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *pair_seeds_t,
+                                const float *fit_t, const uint64_t *hist_pair_seeds, const float *hist_fit,
+                                int32_t hist_len, int32_t N, float sigma, float alpha, float gamma, uint64_t *stats,
+                                void *stream);
 
 /*
  * qes_update / qes_replay_residual with antithetic perturbation pairs (App. A.1): N is even; every

@@ -6,10 +6,10 @@ without a built library raises.
 """
 from .binding import (QesError, Tensor, abi_version, bench_copy, bench_noise, gemm_workspace_bytes,
                       library_path, noise_delta, noise_from_words, noise_gauss, noise_words, normalize_fitness,
-                      perturbed_qgemm, replay_residual, status_string, update, update_full_residual,
+                      perturbed_qgemm, replay_residual, status_string, update, update_batch, update_full_residual,
                       update_stochastic_rounding)
 
 __all__ = ["QesError", "Tensor", "abi_version", "bench_copy", "bench_noise", "gemm_workspace_bytes",
            "library_path", "noise_delta", "noise_from_words", "noise_gauss", "noise_words", "normalize_fitness",
-           "perturbed_qgemm", "replay_residual", "status_string", "update", "update_full_residual",
+           "perturbed_qgemm", "replay_residual", "status_string", "update", "update_batch", "update_full_residual",
            "update_stochastic_rounding"]

@@ -59,6 +59,8 @@ def _load():
         "qes_perturbed_qgemm_antithetic": ([tp, vp, vp, i32, f32, vp, i32, vp, i32, vp, sz, vp], i32),
         "qes_gemm_workspace_bytes": ([tp, i32, i32, i32], sz),
         "qes_update": ([tp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
+        "qes_update_batch": ([vp, i32, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
+        "qes_update_batch_antithetic": ([vp, i32, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
         "qes_replay_residual": ([tp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
         "qes_update_antithetic": ([tp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
         "qes_replay_residual_antithetic": ([tp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
@@ -82,6 +84,7 @@ def _load():
 
 EXPORTS = ["qes_noise_words", "qes_noise_gauss", "qes_noise_delta", "qes_noise_from_words", "qes_perturbed_qgemm",
            "qes_perturbed_qgemm_antithetic", "qes_gemm_workspace_bytes", "qes_update", "qes_update_antithetic",
+           "qes_update_batch", "qes_update_batch_antithetic",
            "qes_replay_residual", "qes_replay_residual_antithetic", "qes_update_full_residual", "qes_update_full_residual_f16",
            "qes_update_stochastic_rounding", "qes_normalize_fitness",
            "qes_bench_noise", "qes_bench_copy", "qes_status_string", "qes_last_hip_error",
@@ -216,6 +219,22 @@ def update(w, seeds_t, fit_t, hist_seeds, hist_fit, sigma, alpha, gamma, stats=N
     fn = _load().qes_update_antithetic if antithetic else _load().qes_update
     _check(fn(ctypes.byref(d), _hptr(seeds_t), _hptr(fit_t), _hptr(hs), _hptr(hf), hl, N, sigma, alpha, gamma,
               _dev_ptr(stats, "stats"), _stream(stream)), "qes_update_antithetic" if antithetic else "qes_update")
+
+
+def update_batch(tensors, seeds_t, fit_t, hist_seeds, hist_fit, sigma, alpha, gamma, stats=None, stream=None,
+                 antithetic=False):
+    """In-place Alg. 2 on every tensor of a list in one call (qes_update_batch): same arguments as update()."""
+    seeds_t = _host(seeds_t, np.uint64)
+    fit_t = _host(fit_t, np.float32)
+    N = int(fit_t.size)
+    if seeds_t.size != (N // 2 if antithetic else N) or (antithetic and N % 2):
+        raise ValueError("seeds_t and fit_t do not match")
+    hs, hf, hl = _hist(hist_seeds, hist_fit, N, antithetic)
+    descs = (_QesTensor * len(tensors))(*[t.desc() for t in tensors])
+    name = "qes_update_batch_antithetic" if antithetic else "qes_update_batch"
+    _check(getattr(_load(), name)(ctypes.cast(descs, ctypes.c_void_p), len(tensors), _hptr(seeds_t), _hptr(fit_t),
+                                  _hptr(hs), _hptr(hf), hl, N, sigma, alpha, gamma, _dev_ptr(stats, "stats"),
+                                  _stream(stream)), name)
 
 
 def replay_residual(w, hist_seeds, hist_fit, N, sigma, alpha, gamma, residual, stream=None, antithetic=False):

@@ -191,6 +191,81 @@ int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit
     return QES_OK;
 }
 
+// Alg. 2 on every tensor of a list in one launch per weight width: the records are staged once,
+// the tensors' descriptors behind them in the same slot.
+int update_batch_common(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *seeds_t, const float *fit_t,
+                        const uint64_t *hist_seeds, const float *hist_fit, int32_t hist_len, int32_t N, float sigma,
+                        float alpha, float gamma, uint64_t *stats, bool antithetic, void *stream)
+{
+    if (!tensors || n_tensors <= 0 || n_tensors > QES_MAX_BATCH) return QES_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        const int rc = tensor_check(&tensors[i]);
+        if (rc != QES_OK) return rc;
+    }
+    if (N <= 0 || N > QES_MAX_POPULATION || hist_len < 0 || hist_len > QES_MAX_HISTORY) return QES_ERR_INVALID_ARG;
+    if (antithetic && (N & 1)) return QES_ERR_INVALID_ARG;
+    if (hist_len > 0 && (!hist_seeds || !hist_fit)) return QES_ERR_INVALID_ARG;
+    if (!seeds_t || !fit_t) return QES_ERR_INVALID_ARG;
+    if (!(sigma > 0.0f) || !std::isfinite(sigma) || !std::isfinite(alpha)) return QES_ERR_INVALID_ARG;
+    if (!(gamma >= 0.0f && gamma <= 1.0f)) return QES_ERR_INVALID_ARG;
+    if (stats && ((uintptr_t)stats & 7u) != 0) return QES_ERR_INVALID_ARG;
+
+    const double c64 = (double)alpha / ((double)N * (double)sigma);
+    const int32_t steps = hist_len + 1;
+    const int32_t records = antithetic ? N / 2 : N;
+    const size_t entry_bytes = (size_t)steps * (size_t)records * sizeof(qes::Entry);
+    const size_t desc_bytes = (size_t)n_tensors * sizeof(qes::TensorDesc);
+    hipStream_t s = (hipStream_t)stream;
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    Slot *slot = nullptr;
+    int rc = acquire_slot(entry_bytes + desc_bytes, &slot);
+    if (rc != QES_OK) return rc;
+    rc = fill_entries((qes::Entry *)slot->host, seeds_t, fit_t, hist_seeds, hist_fit, hist_len, N, antithetic, c64);
+    if (rc != QES_OK) return rc;
+    // descriptors grouped by weight width: [all INT4 tensors][all INT8 tensors], blocks numbered per group
+    qes::TensorDesc *descs = (qes::TensorDesc *)((char *)slot->host + entry_bytes);
+    int32_t count[2] = {0, 0};
+    uint64_t blocks[2] = {0, 0};
+    int32_t at = 0;
+    for (int g = 0; g < 2; ++g) {
+        const int bits = g == 0 ? 4 : 8;
+        for (int32_t i = 0; i < n_tensors; ++i) {
+            const qes_tensor &w = tensors[i];
+            if (w.bits != bits) continue;
+            const uint64_t n_pairs = ((uint64_t)w.out_features * (uint64_t)w.in_features) >> 1;
+            descs[at++] = qes::TensorDesc{w.qweight, (uint32_t)n_pairs, (uint32_t)blocks[g], w.qmin,
+                                          (uint32_t)(w.qmax - w.qmin), w.tensor_id, 0u};
+            blocks[g] += (n_pairs + 255u) / 256u;
+            ++count[g];
+        }
+        if (blocks[g] >= (1ull << 31)) return QES_ERR_UNSUPPORTED;
+    }
+    QES_HIP(hipMemcpyAsync(slot->dev, slot->host, entry_bytes + desc_bytes, hipMemcpyHostToDevice, s));
+
+    qes::UpdateArgs a{};
+    a.entries = (const qes::Entry *)slot->dev;
+    a.stats = (unsigned long long *)stats;
+    a.steps = steps;
+    a.N = records;
+    a.sigma = sigma;
+    a.c = (float)c64;
+    a.gamma = gamma;
+    hipError_t e = hipSuccess;
+    const qes::TensorDesc *dev_descs = (const qes::TensorDesc *)((const char *)slot->dev + entry_bytes);
+    for (int g = 0; g < 2 && e == hipSuccess; ++g) {
+        if (count[g] == 0) continue;
+        a.descs = dev_descs + (g == 0 ? 0 : count[0]);
+        a.n_tensors = count[g];
+        e = qes::launch_update_batch(a, g == 0 ? 4 : 8, antithetic, (uint32_t)blocks[g], s);
+    }
+    hipError_t e2 = hipEventRecord(slot->ev, s);
+    if (e2 == hipSuccess) slot->in_flight = true;
+    else if (e == hipSuccess) e = e2;
+    if (e != hipSuccess) return hip_fail(e);
+    return QES_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -364,6 +439,23 @@ int qes_update_antithetic(qes_tensor *w, const uint64_t *pair_seeds_t, const flo
 {
     return update_common(w, pair_seeds_t, fit_t, hist_pair_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, stats,
                          nullptr, 0, true, stream);
+}
+
+int qes_update_batch(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *seeds_t, const float *fit_t,
+                     const uint64_t *hist_seeds, const float *hist_fit, int32_t hist_len, int32_t N, float sigma,
+                     float alpha, float gamma, uint64_t *stats, void *stream)
+{
+    return update_batch_common(tensors, n_tensors, seeds_t, fit_t, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma,
+                               stats, false, stream);
+}
+
+int qes_update_batch_antithetic(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *pair_seeds_t,
+                                const float *fit_t, const uint64_t *hist_pair_seeds, const float *hist_fit,
+                                int32_t hist_len, int32_t N, float sigma, float alpha, float gamma, uint64_t *stats,
+                                void *stream)
+{
+    return update_batch_common(tensors, n_tensors, pair_seeds_t, fit_t, hist_pair_seeds, hist_fit, hist_len, N, sigma,
+                               alpha, gamma, stats, true, stream);
 }
 
 int qes_replay_residual(const qes_tensor *w, const uint64_t *hist_seeds, const float *hist_fit, int32_t hist_len,

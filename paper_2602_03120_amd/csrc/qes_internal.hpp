@@ -13,6 +13,17 @@ struct Entry {
     uint32_t pad;        // update/replay with antithetic pairs: fitness bits of the -δ member
 };
 
+// One tensor of a batched update launch: its blocks are [first_block, first_block + ceil(n_pairs/256)).
+struct TensorDesc {
+    void *qweight;
+    uint32_t n_pairs;
+    uint32_t first_block;
+    int32_t qmin;
+    uint32_t qspan;
+    uint32_t tensor_id;
+    uint32_t pad;
+};
+
 struct UpdateArgs {
     void *qweight;
     const Entry *entries;        // [steps][N], oldest generation first, current step last
@@ -26,6 +37,8 @@ struct UpdateArgs {
     uint32_t qspan;              // qmax - qmin
     uint32_t tensor_id;
     uint32_t round_k0, round_k1; // stochastic-rounding baseline: key of the step's rounding stream
+    const TensorDesc *descs;     // batched launch: per-tensor fields above come from here
+    int32_t n_tensors;
 };
 
 struct GemmArgs {
@@ -57,6 +70,8 @@ hipError_t launch_bench_copy(const void *src, void *dst, size_t n_bytes, hipStre
 
 // bits: 4|8; rmode 0: Alg. 2 in place; 1: replay only, residual written; 2: Alg. 1 step on a stored residual
 hipError_t launch_update(const UpdateArgs &a, int bits, int rmode, bool antithetic, hipStream_t s);
+// Alg. 2 on several tensors of one width in one launch (a.descs, a.n_tensors; total_blocks = sum of their blocks)
+hipError_t launch_update_batch(const UpdateArgs &a, int bits, bool antithetic, uint32_t total_blocks, hipStream_t s);
 
 hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_scale, int64_t rows,
                                        int32_t in_features, hipStream_t s);

@@ -103,12 +103,31 @@ struct Raw {
 // stream keyed by the step's rounding seed, stream tag 1).
 // A thread owns PPT pairs and regenerates the noise of MI members at a time: PPT*MI independent
 // Philox/Box-Muller chains in flight per thread, while the sum of Eq. 5 still runs in member order.
-template <int BITS, int PPT, int MI, int RMODE, bool CLAMP, bool ANTI>
-__global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs a)
+// BATCH: one launch covers several tensors (same seeds, fitnesses and history: the whole model's
+// update is one call); a block finds its tensor by bisection over the tensors' first blocks.
+template <int BITS, int PPT, int MI, int RMODE, bool CLAMP, bool ANTI, bool BATCH>
+__global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs args)
 {
     using P = Pack<BITS>;
     constexpr int kBytes = PPT * P::kBytesPerPair;
-    const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+    UpdateArgs a = args;
+    uint32_t block = blockIdx.x;
+    if (BATCH) {
+        int lo = 0, hi = args.n_tensors - 1;   // wave-uniform: scalar loads
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (args.descs[mid].first_block <= block) lo = mid;
+            else hi = mid - 1;
+        }
+        const TensorDesc td = args.descs[lo];
+        a.qweight = td.qweight;
+        a.n_pairs = td.n_pairs;
+        a.qmin = td.qmin;
+        a.qspan = td.qspan;
+        a.tensor_id = td.tensor_id;
+        block -= td.first_block;
+    }
+    const uint32_t t = block * kBlock + threadIdx.x;
     const uint32_t pair0 = t * PPT;
     if (pair0 >= a.n_pairs) return;   // n_pairs is a multiple of PPT (checked on the host)
 
@@ -254,11 +273,27 @@ hipError_t launch_variant(const UpdateArgs &a, bool antithetic, hipStream_t s)
     const bool clamp = !(a.sigma <= 1.2f);
     constexpr int P = kPairsPerThread, M = kMembersAtATime;
     if (clamp) {
-        if (antithetic) update_kernel<BITS, P, M, RMODE, true, true><<<blocks, kBlock, 0, s>>>(a);
-        else update_kernel<BITS, P, M, RMODE, true, false><<<blocks, kBlock, 0, s>>>(a);
+        if (antithetic) update_kernel<BITS, P, M, RMODE, true, true, false><<<blocks, kBlock, 0, s>>>(a);
+        else update_kernel<BITS, P, M, RMODE, true, false, false><<<blocks, kBlock, 0, s>>>(a);
     } else {
-        if (antithetic) update_kernel<BITS, P, M, RMODE, false, true><<<blocks, kBlock, 0, s>>>(a);
-        else update_kernel<BITS, P, M, RMODE, false, false><<<blocks, kBlock, 0, s>>>(a);
+        if (antithetic) update_kernel<BITS, P, M, RMODE, false, true, false><<<blocks, kBlock, 0, s>>>(a);
+        else update_kernel<BITS, P, M, RMODE, false, false, false><<<blocks, kBlock, 0, s>>>(a);
+    }
+    return hipGetLastError();
+}
+
+template <int BITS>
+hipError_t launch_batch_variant(const UpdateArgs &a, bool antithetic, uint32_t total_blocks, hipStream_t s)
+{
+    static_assert(kPairsPerThread == 1, "the host lays out ceil(n_pairs / 256) blocks per tensor");
+    const bool clamp = !(a.sigma <= 1.2f);
+    constexpr int P = kPairsPerThread, M = kMembersAtATime;
+    if (clamp) {
+        if (antithetic) update_kernel<BITS, P, M, 0, true, true, true><<<total_blocks, kBlock, 0, s>>>(a);
+        else update_kernel<BITS, P, M, 0, true, false, true><<<total_blocks, kBlock, 0, s>>>(a);
+    } else {
+        if (antithetic) update_kernel<BITS, P, M, 0, false, true, true><<<total_blocks, kBlock, 0, s>>>(a);
+        else update_kernel<BITS, P, M, 0, false, false, true><<<total_blocks, kBlock, 0, s>>>(a);
     }
     return hipGetLastError();
 }
@@ -284,6 +319,13 @@ hipError_t launch_update(const UpdateArgs &a, int bits, int rmode, bool antithet
     case 3: return launch_variant<8, 3>(a, antithetic, s);
     default: return launch_variant<8, 4>(a, antithetic, s);
     }
+}
+
+hipError_t launch_update_batch(const UpdateArgs &a, int bits, bool antithetic, uint32_t total_blocks, hipStream_t s)
+{
+    if (total_blocks == 0) return hipSuccess;
+    return bits == 4 ? launch_batch_variant<4>(a, antithetic, total_blocks, s)
+                     : launch_batch_variant<8>(a, antithetic, total_blocks, s);
 }
 
 }  // namespace qes
