@@ -39,8 +39,9 @@ MFMA_PEAK = {"bf16": 2.5e15, "i8": 5.0e15}
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this file, scaled by the same counters on the plain copy issued below (see profiles/):
-# {(config, tensor name): bytes}. A launch covers one tensor, whatever --layers says.
-MEASURED_TRAFFIC_BYTES = {(2, "gate"): 2.374e6, (3, "gate"): 7.223e6}
+# {(config, what one launch covers): bytes}: one layer's linears (qes_update_batch), or one tensor
+# with --per-tensor-update. A launch covers that much whatever --layers says.
+MEASURED_TRAFFIC_BYTES = {(2, "layer"): 6.79e6, (3, "layer"): 24.06e6, (2, "gate"): 2.374e6, (3, "gate"): 7.223e6}
 
 
 def parse():
