@@ -53,6 +53,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="limit the number of layers (debug)")
     ap.add_argument("--K", type=int, default=None, help="override the replay window of the configuration")
     ap.add_argument("--N", type=int, default=None, help="override the population of the configuration")
+    ap.add_argument("--per-tensor-gemm", action="store_true",
+                    help="one qes_perturbed_qgemm call per tensor instead of one qes_perturbed_qgemm_batch call per layer")
     ap.add_argument("--per-tensor-update", action="store_true",
                     help="one qes_update call per tensor instead of one qes_update_batch call per layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -103,9 +105,12 @@ def main():
         if spec.x_key not in xs:
             xb = wl.make_activations(cfg, spec.x_key, spec.in_features)
             xs[spec.x_key] = torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16)
-    ys = {spec.out_features: torch.empty((cfg.N, cfg.T, spec.out_features), dtype=torch.bfloat16, device=dev)
-          for spec in cfg.linears}
-    ws_bytes = max(qes.gemm_workspace_bytes(t, cfg.N, cfg.T, cfg.act_mode) for _, _, t in tensors)
+    layer_tensors = [[t for la, _, t in tensors if la == layer] for layer in range(n_layers)]
+    layer_xs = [xs[spec.x_key] for spec in cfg.linears]
+    # a batched launch writes all outputs of a layer at once: one buffer per linear
+    layer_ys = [torch.empty((cfg.N, cfg.T, spec.out_features), dtype=torch.bfloat16, device=dev) for spec in cfg.linears]
+    ws_bytes = max(max(qes.gemm_workspace_bytes(t, cfg.N, cfg.T, cfg.act_mode) for _, _, t in tensors),
+                   qes.gemm_batch_workspace_bytes(layer_tensors[0], layer_xs, cfg.N, cfg.T, cfg.act_mode))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
     stats = torch.zeros(2, dtype=torch.int64, device=dev)
     # one plain copy of known size before the timed region: the reference dispatch that scales the
@@ -126,7 +131,6 @@ def main():
     rewards = wl.make_rewards(cfg, cfg.K + total_steps)
     fits = np.stack([qes.normalize_fitness(r) for r in rewards])
 
-    layer_tensors = [[t for la, _, t in tensors if la == layer] for layer in range(n_layers)]
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
     gemm_events, upd_events = [], []
 
@@ -134,10 +138,16 @@ def main():
         # population evaluation: every linear, every member
         g0, g1 = ev(), ev()
         g0.record()
-        for layer, li, t in tensors:
-            spec = cfg.linears[li]
-            qes.perturbed_qgemm(t, seeds[cfg.K + s], cfg.sigma, xs[spec.x_key], ys[spec.out_features],
-                                act_mode=cfg.act_mode, workspace=ws, antithetic=anti)
+        if args.per_tensor_gemm:
+            for layer, li, t in tensors:
+                spec = cfg.linears[li]
+                qes.perturbed_qgemm(t, seeds[cfg.K + s], cfg.sigma, xs[spec.x_key], layer_ys[li],
+                                    act_mode=cfg.act_mode, workspace=ws, antithetic=anti)
+        else:
+            # the linears of a layer share members and token count: one launch per layer
+            for layer in range(n_layers):
+                qes.perturbed_qgemm_batch(layer_tensors[layer], seeds[cfg.K + s], cfg.sigma, layer_xs, layer_ys,
+                                          act_mode=cfg.act_mode, workspace=ws, antithetic=anti)
         g1.record()
         # seeded update with a full replay window (steady state: K generations of history): all
         # linears of a layer share the generation's records and go in one call
@@ -222,8 +232,9 @@ def main():
         "config": {"workload": "config %d: %s (%d layers of %s), N=%d, T=%d, K=%d, sigma=%g, alpha=%g, gamma=%g"
                    % (cfg.index, cfg.name, n_layers, "/".join(l.name for l in cfg.linears), cfg.N, cfg.T, cfg.K,
                       cfg.sigma, cfg.alpha, cfg.gamma),
-                   "parameters": params, "step": "perturbed qGEMM of every linear + update with full replay window (%s)"
-                   % ("one call per tensor" if args.per_tensor_update else "one call per layer"),
+                   "parameters": params, "step": "perturbed qGEMM of every linear + update with full replay window; %s"
+                   % ("GEMM: one call per %s, update: one call per %s"
+                      % ("tensor" if args.per_tensor_gemm else "layer", "tensor" if args.per_tensor_update else "layer")),
                    "antithetic_pairs": bool(anti)},
         "roofline": {
             "kernel": dom_name,

@@ -41,7 +41,7 @@ typedef enum {
 /* Limits of the small HOST arrays. */
 #define QES_MAX_POPULATION 1024 /* N */
 #define QES_MAX_HISTORY 256     /* hist_len */
-#define QES_MAX_BATCH 4096      /* tensors per qes_update_batch call */
+#define QES_MAX_BATCH 4096      /* tensors per qes_update_batch / qes_perturbed_qgemm_batch call */
 
 /*
  * One quantised linear weight (App. A.1; INT4 group-scaled and INT8 per-output-channel formats).
@@ -144,6 +144,31 @@ int qes_perturbed_qgemm_antithetic(const qes_tensor *w, const uint64_t *pair_see
 
 /* Bytes of DEVICE workspace qes_perturbed_qgemm needs for these arguments (0 for act_mode 0). */
 size_t qes_gemm_workspace_bytes(const qes_tensor *w, int32_t N, int32_t T, int32_t act_mode);
+
+/*
+ * qes_perturbed_qgemm for every tensor of a list (the linears of a layer: same members, same token
+ * count, each with its own activations and outputs) in one launch per weight width: the workgroups
+ * of all tensors fill the chip together instead of each launch ending in a partly filled round.
+ * Results are bit-identical to n_tensors single calls.
+ *
+ *   tensors   HOST array [n_tensors] of descriptors, 1 <= n_tensors <= QES_MAX_BATCH
+ *   x, y      HOST arrays [n_tensors] of DEVICE pointers: x[i] bfloat16 [N, T, in_features of tensor i],
+ *             y[i] bfloat16 [N, T, out_features of tensor i]. Tensors may share an x (q/k/v, gate/up);
+ *             with act_mode 1 a shared x is quantised once.
+ *   workspace at least qes_gemm_batch_workspace_bytes() bytes (0 for act_mode 0)
+ * Other arguments, requirements and errors as for qes_perturbed_qgemm(_antithetic).
+ */
+int qes_perturbed_qgemm_batch(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *seeds,
+                              const uint8_t *perturb_mask, int32_t N, float sigma, const void *const *x, int32_t T,
+                              void *const *y, int32_t act_mode, void *workspace, size_t workspace_bytes, void *stream);
+
+int qes_perturbed_qgemm_batch_antithetic(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *pair_seeds,
+                                         const uint8_t *perturb_mask, int32_t N, float sigma, const void *const *x,
+                                         int32_t T, void *const *y, int32_t act_mode, void *workspace,
+                                         size_t workspace_bytes, void *stream);
+
+size_t qes_gemm_batch_workspace_bytes(const qes_tensor *tensors, int32_t n_tensors, const void *const *x, int32_t N,
+                                      int32_t T, int32_t act_mode);
 
 /* ---- the seeded update (Alg. 2 whole; Eq. 5-8) ---- */
 

@@ -59,6 +59,9 @@ def _load():
         "qes_perturbed_qgemm_antithetic": ([tp, vp, vp, i32, f32, vp, i32, vp, i32, vp, sz, vp], i32),
         "qes_gemm_workspace_bytes": ([tp, i32, i32, i32], sz),
         "qes_update": ([tp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
+        "qes_perturbed_qgemm_batch": ([vp, i32, vp, vp, i32, f32, vp, i32, vp, i32, vp, sz, vp], i32),
+        "qes_perturbed_qgemm_batch_antithetic": ([vp, i32, vp, vp, i32, f32, vp, i32, vp, i32, vp, sz, vp], i32),
+        "qes_gemm_batch_workspace_bytes": ([vp, i32, vp, i32, i32, i32], sz),
         "qes_update_batch": ([vp, i32, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
         "qes_update_batch_antithetic": ([vp, i32, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
         "qes_replay_residual": ([tp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
@@ -83,7 +86,8 @@ def _load():
 
 
 EXPORTS = ["qes_noise_words", "qes_noise_gauss", "qes_noise_delta", "qes_noise_from_words", "qes_perturbed_qgemm",
-           "qes_perturbed_qgemm_antithetic", "qes_gemm_workspace_bytes", "qes_update", "qes_update_antithetic",
+           "qes_perturbed_qgemm_antithetic", "qes_gemm_workspace_bytes", "qes_perturbed_qgemm_batch",
+           "qes_perturbed_qgemm_batch_antithetic", "qes_gemm_batch_workspace_bytes", "qes_update", "qes_update_antithetic",
            "qes_update_batch", "qes_update_batch_antithetic",
            "qes_replay_residual", "qes_replay_residual_antithetic", "qes_update_full_residual", "qes_update_full_residual_f16",
            "qes_update_stochastic_rounding", "qes_normalize_fitness",
@@ -194,6 +198,41 @@ def perturbed_qgemm(w, seeds, sigma, x, y, act_mode=0, perturb_mask=None, worksp
     _check(fn(ctypes.byref(d), _hptr(seeds), _hptr(mask), N, sigma, _dev_ptr(x, "x"), T, _dev_ptr(y, "y"), act_mode,
               _dev_ptr(workspace, "workspace"), ws_bytes, _stream(stream)),
            "qes_perturbed_qgemm_antithetic" if antithetic else "qes_perturbed_qgemm")
+
+
+def _batch_arrays(tensors, xs, ys=None):
+    descs = (_QesTensor * len(tensors))(*[t.desc() for t in tensors])
+    xp = (ctypes.c_void_p * len(tensors))(*[_dev_ptr(x, "x") for x in xs])
+    yp = None if ys is None else (ctypes.c_void_p * len(tensors))(*[_dev_ptr(y, "y") for y in ys])
+    return descs, xp, yp
+
+
+def gemm_batch_workspace_bytes(tensors, xs, N, T, act_mode):
+    descs, xp, _ = _batch_arrays(tensors, xs)
+    return int(_load().qes_gemm_batch_workspace_bytes(ctypes.cast(descs, ctypes.c_void_p), len(tensors),
+                                                      ctypes.cast(xp, ctypes.c_void_p), N, T, act_mode))
+
+
+def perturbed_qgemm_batch(tensors, seeds, sigma, xs, ys, act_mode=0, perturb_mask=None, workspace=None, stream=None,
+                          antithetic=False):
+    """perturbed_qgemm for a list of tensors in one call: xs[i] device bf16 [N,T,in_i] (tensors may share
+    one), ys[i] device bf16 [N,T,out_i] (written)."""
+    seeds = _host(seeds, np.uint64)
+    mask = _host(perturb_mask, np.uint8)
+    if len(tensors) == 0 or len(xs) != len(tensors) or len(ys) != len(tensors):
+        raise ValueError("tensors, xs and ys differ in length")
+    N, T = int(xs[0].shape[0]), int(xs[0].shape[1])
+    if seeds.size != (N // 2 if antithetic else N) or (mask is not None and mask.size != N) or (antithetic and N % 2):
+        raise ValueError("seeds / perturb_mask do not match the population")
+    for w, x, y in zip(tensors, xs, ys):
+        if tuple(x.shape) != (N, T, w.in_features) or tuple(y.shape) != (N, T, w.out_features):
+            raise ValueError("x / y shapes do not match the tensor")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    descs, xp, yp = _batch_arrays(tensors, xs, ys)
+    name = "qes_perturbed_qgemm_batch_antithetic" if antithetic else "qes_perturbed_qgemm_batch"
+    _check(getattr(_load(), name)(ctypes.cast(descs, ctypes.c_void_p), len(tensors), _hptr(seeds), _hptr(mask), N, sigma,
+                                  ctypes.cast(xp, ctypes.c_void_p), T, ctypes.cast(yp, ctypes.c_void_p), act_mode,
+                                  _dev_ptr(workspace, "workspace"), ws_bytes, _stream(stream)), name)
 
 
 def _hist(hist_seeds, hist_fit, N, antithetic=False):

@@ -1,8 +1,10 @@
 // C ABI of libqes (declared in include/qes.h): argument validation, staging of the small host
 // arrays (seeds, fitnesses) into device memory in stream order, kernel launches.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <vector>
 
 #include "../../include/qes.h"
 #include "qes_internal.hpp"
@@ -333,14 +335,15 @@ size_t qes_gemm_workspace_bytes(const qes_tensor *w, int32_t N, int32_t T, int32
     return xq + rows * sizeof(float);
 }
 
-static int gemm_common(const qes_tensor *w, const uint64_t *seeds, const uint8_t *perturb_mask, int32_t N,
-                       float sigma, const void *x, int32_t T, void *y, int32_t act_mode, void *workspace,
-                       size_t workspace_bytes, bool antithetic, void *stream)
+// Validation of one tensor's GEMM arguments and the kernel arguments that follow from them
+// (activations and entries are filled in by the caller).
+static int gemm_prepare(const qes_tensor *w, const void *x, void *y, int32_t N, int32_t T, float sigma, int32_t act_mode,
+                        bool antithetic, qes::GemmArgs *out)
 {
     int rc = tensor_check(w);
     if (rc != QES_OK) return rc;
     if (antithetic && (N & 1)) return QES_ERR_INVALID_ARG;
-    if (!w->scales || !seeds || !x || !y || N <= 0 || N > QES_MAX_POPULATION || T <= 0) return QES_ERR_INVALID_ARG;
+    if (!w->scales || !x || !y || N <= 0 || N > QES_MAX_POPULATION || T <= 0) return QES_ERR_INVALID_ARG;
     if (((uintptr_t)x & 15u) != 0 || ((uintptr_t)y & 1u) != 0 || ((uintptr_t)w->scales & 1u) != 0)
         return QES_ERR_INVALID_ARG;
     if (!(sigma >= 0.0f) || !std::isfinite(sigma)) return QES_ERR_INVALID_ARG;
@@ -350,8 +353,6 @@ static int gemm_common(const qes_tensor *w, const uint64_t *seeds, const uint8_t
     // one member's activations are addressed with 32-bit byte offsets inside the kernel
     if ((uint64_t)T * (uint64_t)w->in_features * 2u >= (1ull << 32)) return QES_ERR_UNSUPPORTED;
     if ((uint64_t)N * (uint64_t)T * (uint64_t)w->in_features >= (1ull << 40)) return QES_ERR_UNSUPPORTED;
-    hipStream_t s = (hipStream_t)stream;
-
     qes::GemmArgs a{};
     a.qweight = w->qweight;
     a.scales = w->scales;
@@ -367,6 +368,47 @@ static int gemm_common(const qes_tensor *w, const uint64_t *seeds, const uint8_t
     a.qmin = w->qmin;
     a.qspan = (uint32_t)(w->qmax - w->qmin);
     a.tensor_id = w->tensor_id;
+    *out = a;
+    return QES_OK;
+}
+
+// bytes of one quantised activation tensor [rows, in_features] int8 + its per-row scales
+static size_t quantised_bytes(size_t rows, int32_t in_features)
+{
+    return ((rows * (size_t)in_features + 15u) & ~(size_t)15u) + ((rows * sizeof(float) + 15u) & ~(size_t)15u);
+}
+
+// One record per member, or per antithetic pair when a workgroup serves both members of a pair
+// from one draw (then bit 0 / bit 1 of the mode say which member is perturbed); otherwise mode
+// 0 = base weights, 1 = +δ, 2 = -δ (mirrored member regenerating its pair's draw).
+static int32_t fill_gemm_entries(qes::Entry *ent, const uint64_t *seeds, const uint8_t *perturb_mask, int32_t N,
+                                 bool antithetic, bool paired)
+{
+    const int32_t records = paired ? N / 2 : N;
+    auto on = [&](int32_t i) { return !(perturb_mask != nullptr && perturb_mask[i] == 0); };
+    for (int32_t i = 0; i < records; ++i) {
+        if (paired) {
+            const uint64_t sd = seeds[i];
+            const uint32_t mode = (on(2 * i) ? 1u : 0u) | (on(2 * i + 1) ? 2u : 0u);
+            ent[i] = qes::Entry{(uint32_t)sd, (uint32_t)(sd >> 32), mode, 0u};
+        } else {
+            const uint64_t sd = antithetic ? seeds[i / 2] : seeds[i];
+            const uint32_t mode = !on(i) ? 0u : ((antithetic && (i & 1)) ? 2u : 1u);
+            ent[i] = qes::Entry{(uint32_t)sd, (uint32_t)(sd >> 32), mode, 0u};
+        }
+    }
+    return records;
+}
+
+static int gemm_common(const qes_tensor *w, const uint64_t *seeds, const uint8_t *perturb_mask, int32_t N,
+                       float sigma, const void *x, int32_t T, void *y, int32_t act_mode, void *workspace,
+                       size_t workspace_bytes, bool antithetic, void *stream)
+{
+    if (!seeds) return QES_ERR_INVALID_ARG;
+    qes::GemmArgs a{};
+    int rc = gemm_prepare(w, x, y, N, T, sigma, act_mode, antithetic, &a);
+    if (rc != QES_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
 
     if (act_mode == 1) {
         const size_t need = qes_gemm_workspace_bytes(w, N, T, act_mode);
@@ -383,26 +425,134 @@ static int gemm_common(const qes_tensor *w, const uint64_t *seeds, const uint8_t
     Slot *slot = nullptr;
     rc = acquire_slot((size_t)N * sizeof(qes::Entry), &slot);
     if (rc != QES_OK) return rc;
-    qes::Entry *ent = (qes::Entry *)slot->host;
     // antithetic pairs share one draw inside a workgroup when both members' accumulators fit
-    // and two workgroups still share a CU; longer token counts regenerate the draw per member (mode 2 = -δ)
+    // and two workgroups still share a CU; longer token counts regenerate the draw per member
     const bool paired = antithetic && qes::gemm_pairs_supported(T);
-    const int32_t records = paired ? N / 2 : N;
-    auto on = [&](int32_t i) { return !(perturb_mask != nullptr && perturb_mask[i] == 0); };
-    for (int32_t i = 0; i < records; ++i) {
-        if (paired) {
-            const uint64_t sd = seeds[i];
-            const uint32_t mode = (on(2 * i) ? 1u : 0u) | (on(2 * i + 1) ? 2u : 0u);
-            ent[i] = qes::Entry{(uint32_t)sd, (uint32_t)(sd >> 32), mode, 0u};
-        } else {
-            const uint64_t sd = antithetic ? seeds[i / 2] : seeds[i];
-            const uint32_t mode = !on(i) ? 0u : ((antithetic && (i & 1)) ? 2u : 1u);
-            ent[i] = qes::Entry{(uint32_t)sd, (uint32_t)(sd >> 32), mode, 0u};
-        }
-    }
+    const int32_t records = fill_gemm_entries((qes::Entry *)slot->host, seeds, perturb_mask, N, antithetic, paired);
     QES_HIP(hipMemcpyAsync(slot->dev, slot->host, (size_t)records * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
     a.entries = (const qes::Entry *)slot->dev;
     hipError_t e = qes::launch_gemm(a, w->bits, act_mode, paired, s);
+    hipError_t e2 = hipEventRecord(slot->ev, s);
+    if (e2 == hipSuccess) slot->in_flight = true;
+    else if (e == hipSuccess) e = e2;
+    if (e != hipSuccess) return hip_fail(e);
+    return QES_OK;
+}
+
+// The distinct activation tensors of a batch (linears of a layer share inputs): index of x[i] in
+// the list of distinct (pointer, in_features) pairs, in order of first appearance.
+static int32_t distinct_inputs(const qes_tensor *tensors, int32_t n, const void *const *x, int32_t *which)
+{
+    int32_t n_distinct = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        int32_t found = -1;
+        for (int32_t j = 0; j < i && found < 0; ++j)
+            if (x[j] == x[i] && tensors[j].in_features == tensors[i].in_features) found = which[j];
+        which[i] = found >= 0 ? found : n_distinct++;
+    }
+    return n_distinct;
+}
+
+size_t qes_gemm_batch_workspace_bytes(const qes_tensor *tensors, int32_t n_tensors, const void *const *x, int32_t N,
+                                      int32_t T, int32_t act_mode)
+{
+    if (!tensors || !x || n_tensors <= 0 || n_tensors > QES_MAX_BATCH || act_mode != 1 || N <= 0 || T <= 0) return 0;
+    std::vector<int32_t> which((size_t)n_tensors);
+    const int32_t n_distinct = distinct_inputs(tensors, n_tensors, x, which.data());
+    size_t total = 0;
+    for (int32_t d = 0; d < n_distinct; ++d)
+        for (int32_t i = 0; i < n_tensors; ++i)
+            if (which[i] == d) {
+                total += quantised_bytes((size_t)N * (size_t)T, tensors[i].in_features);
+                break;
+            }
+    return total;
+}
+
+static int gemm_batch_common(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *seeds,
+                             const uint8_t *perturb_mask, int32_t N, float sigma, const void *const *x, int32_t T,
+                             void *const *y, int32_t act_mode, void *workspace, size_t workspace_bytes, bool antithetic,
+                             void *stream)
+{
+    if (!tensors || !x || !y || !seeds || n_tensors <= 0 || n_tensors > QES_MAX_BATCH) return QES_ERR_INVALID_ARG;
+    std::vector<qes::GemmArgs> args((size_t)n_tensors);
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        const int rc = gemm_prepare(&tensors[i], x[i], y[i], N, T, sigma, act_mode, antithetic, &args[(size_t)i]);
+        if (rc != QES_OK) return rc;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const size_t rows = (size_t)N * (size_t)T;
+
+    if (act_mode == 1) {
+        // every distinct activation tensor is quantised once
+        const size_t need = qes_gemm_batch_workspace_bytes(tensors, n_tensors, x, N, T, act_mode);
+        if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15u) != 0) return QES_ERR_WORKSPACE;
+        std::vector<int32_t> which((size_t)n_tensors);
+        const int32_t n_distinct = distinct_inputs(tensors, n_tensors, x, which.data());
+        std::vector<char *> region((size_t)n_distinct, nullptr);
+        char *at = (char *)workspace;
+        for (int32_t i = 0; i < n_tensors; ++i) {
+            const int32_t in_f = tensors[i].in_features;
+            char *&r = region[(size_t)which[i]];
+            if (!r) {
+                r = at;
+                at += quantised_bytes(rows, in_f);
+                float *xs = (float *)(r + ((rows * (size_t)in_f + 15u) & ~(size_t)15u));
+                QES_HIP(qes::launch_quantize_activations(x[i], (int8_t *)r, xs, (int64_t)rows, in_f, s));
+            }
+            args[(size_t)i].x = r;
+            args[(size_t)i].x_scale = (const float *)(r + ((rows * (size_t)in_f + 15u) & ~(size_t)15u));
+        }
+    }
+
+    const bool paired = antithetic && qes::gemm_pairs_supported(T);
+    const int32_t records = paired ? N / 2 : N;
+    const size_t entry_bytes = (size_t)records * sizeof(qes::Entry);
+    const size_t desc_bytes = (size_t)n_tensors * sizeof(qes::GemmArgs);
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    Slot *slot = nullptr;
+    int rc = acquire_slot(entry_bytes + desc_bytes, &slot);
+    if (rc != QES_OK) return rc;
+    fill_gemm_entries((qes::Entry *)slot->host, seeds, perturb_mask, N, antithetic, paired);
+    // Descriptors grouped by weight width; inside a group the tensors with the longest rows first
+    // (their workgroups run longest, the short ones then fill the end of the launch). Each tensor
+    // takes ceil(W/8) slots in every XCD's queue.
+    qes::GemmArgs *descs = (qes::GemmArgs *)((char *)slot->host + entry_bytes);
+    int32_t count[2] = {0, 0};
+    uint64_t work[2] = {0, 0};
+    int32_t at = 0;
+    std::vector<int32_t> order;
+    for (int g = 0; g < 2; ++g) {
+        const int bits = g == 0 ? 4 : 8;
+        order.clear();
+        for (int32_t i = 0; i < n_tensors; ++i)
+            if (tensors[i].bits == bits) order.push_back(i);
+        std::stable_sort(order.begin(), order.end(),
+                         [&](int32_t p, int32_t q) { return tensors[p].in_features > tensors[q].in_features; });
+        for (int32_t i : order) {
+            qes::GemmArgs d = args[(size_t)i];
+            d.entries = (const qes::Entry *)slot->dev;
+            d.work_begin = (uint32_t)work[g];
+            work[g] += (qes::gemm_work_items(d.out_features, N, paired) + 7u) / 8u;
+            descs[at++] = d;
+            ++count[g];
+        }
+        if (work[g] >= (1ull << 27)) return QES_ERR_UNSUPPORTED;
+    }
+    QES_HIP(hipMemcpyAsync(slot->dev, slot->host, entry_bytes + desc_bytes, hipMemcpyHostToDevice, s));
+    const qes::GemmArgs *dev_descs = (const qes::GemmArgs *)((const char *)slot->dev + entry_bytes);
+    hipError_t e = hipSuccess;
+    for (int g = 0; g < 2 && e == hipSuccess; ++g) {
+        if (count[g] == 0) continue;
+        qes::GemmArgs a{};
+        a.N = N;
+        a.T = T;
+        a.batch = dev_descs + (g == 0 ? 0 : count[0]);
+        a.n_batch = count[g];
+        a.work_begin = (uint32_t)work[g];   // slots per XCD queue of this launch
+        e = qes::launch_gemm(a, g == 0 ? 4 : 8, act_mode, paired, s);
+    }
     hipError_t e2 = hipEventRecord(slot->ev, s);
     if (e2 == hipSuccess) slot->in_flight = true;
     else if (e == hipSuccess) e = e2;
@@ -423,6 +573,23 @@ int qes_perturbed_qgemm_antithetic(const qes_tensor *w, const uint64_t *pair_see
 {
     return gemm_common(w, pair_seeds, perturb_mask, N, sigma, x, T, y, act_mode, workspace, workspace_bytes, true,
                        stream);
+}
+
+int qes_perturbed_qgemm_batch(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *seeds,
+                              const uint8_t *perturb_mask, int32_t N, float sigma, const void *const *x, int32_t T,
+                              void *const *y, int32_t act_mode, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gemm_batch_common(tensors, n_tensors, seeds, perturb_mask, N, sigma, x, T, y, act_mode, workspace,
+                             workspace_bytes, false, stream);
+}
+
+int qes_perturbed_qgemm_batch_antithetic(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *pair_seeds,
+                                         const uint8_t *perturb_mask, int32_t N, float sigma, const void *const *x,
+                                         int32_t T, void *const *y, int32_t act_mode, void *workspace,
+                                         size_t workspace_bytes, void *stream)
+{
+    return gemm_batch_common(tensors, n_tensors, pair_seeds, perturb_mask, N, sigma, x, T, y, act_mode, workspace,
+                             workspace_bytes, true, stream);
 }
 
 int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,

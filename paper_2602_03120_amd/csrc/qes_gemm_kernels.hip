@@ -51,6 +51,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
+// Kernel arguments and batch descriptors are read through the constant address space: wave-uniform
+// reads from it are scalar loads issued where a field is needed, so the fields never occupy
+// registers for long (a by-value copy of the 100-byte argument block would).
+typedef const __attribute__((address_space(4))) GemmArgs ConstGemmArgs;
 
 constexpr int kRG = 4;          // row groups (of 16 output rows) per workgroup
 constexpr int kWaves = 8;       // waves per workgroup
@@ -86,15 +90,16 @@ __device__ __forceinline__ float f16_bits_to_f32(uint16_t h)
 // XCD-aware block -> (member, n-tile): consecutive work items (same member, neighbouring tiles)
 // land on the same XCD (blocks are dealt round-robin over 8 XCDs), so a member's activations stay
 // in one L2.
-__device__ __forceinline__ bool block_to_work(uint32_t n_tiles, uint32_t n_members, uint32_t &member, uint32_t &tile)
+__device__ __forceinline__ uint32_t gemm_work_items_device(int32_t out_features, int32_t N, bool paired)
 {
-    const uint32_t total = n_tiles * n_members;
+    return (uint32_t)((out_features + kTileN - 1) / kTileN) * ((uint32_t)N / (paired ? 2u : 1u));
+}
+
+__device__ __forceinline__ bool block_to_index(uint32_t total, uint32_t &idx)
+{
     const uint32_t per_xcd = (total + 7u) / 8u;
-    const uint32_t idx = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-    if ((blockIdx.x >> 3) >= per_xcd || idx >= total) return false;
-    member = idx / n_tiles;
-    tile = idx - member * n_tiles;
-    return true;
+    idx = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    return (blockIdx.x >> 3) < per_xcd && idx < total;
 }
 
 // One pair of elements for both members of an antithetic pair: one draw; the even member gates
@@ -156,7 +161,7 @@ struct Gemm {
     static constexpr int kWBytesPerSub = (MODE == kBf16W4) ? 16 : (MODE == kBf16W8 ? 32 : 64);   // weight bytes per row and substep
     using Acc = typename std::conditional<kI8, i32x4, f32x4>::type;
 
-    const GemmArgs &a;
+    ConstGemmArgs &a;
     Entry en;
     int lane, wave, wm, wr, ln, kc, n_sub;
     int jrg, jhalf;               // noise job of this wave: half `jhalf` of row group `jrg`'s fragment
@@ -454,9 +459,11 @@ struct Gemm {
     }
 };
 
-template <int MODE, int TM, bool PAIRED>
-// register budget: two workgroups per CU (4 waves per SIMD) also for the largest accumulator sets
-__global__ __launch_bounds__(kThreads, ((!PAIRED && TM >= 512) || (PAIRED && TM == 128) ? 4 : 1)) void gemm_kernel(const GemmArgs a)
+// BATCH: one launch covers several tensors (a layer's linears: same members, same token count);
+// a block finds its tensor by bisection over the tensors' first slots in the per-XCD queues.
+// Register budget: two workgroups per CU (4 waves per SIMD) also for the largest accumulator sets.
+template <int MODE, int TM, bool PAIRED, bool BATCH>
+__global__ __launch_bounds__(kThreads, ((!PAIRED && TM >= 512) || (PAIRED && TM == 128) ? 4 : 1)) void gemm_kernel(const GemmArgs args)
 {
     using G = Gemm<MODE, TM, PAIRED>;
     constexpr int kP = G::kP;
@@ -467,9 +474,33 @@ __global__ __launch_bounds__(kThreads, ((!PAIRED && TM >= 512) || (PAIRED && TM 
     __shared__ __attribute__((aligned(16))) char bfrag[2 * kP * kFragBytes];
 
     // work item: a member, or an antithetic pair of members (PAIRED; a.entries then holds one record per pair)
-    uint32_t member, tile;
+    // this kernel's only parameter sits at the start of the kernel-argument segment
+    ConstGemmArgs *ap = (ConstGemmArgs *)__builtin_amdgcn_kernarg_segment_ptr();
+    uint32_t idx = 0;
+    if (BATCH) {
+        // Blocks are dealt round-robin over the 8 XCDs; XCD x runs slots 0, 1, 2, ... of its own
+        // queue. Every tensor puts an eighth of its work items (a contiguous range, so that a
+        // member's tiles share an L2) into each queue, one tensor after the other.
+        ConstGemmArgs *descs = (ConstGemmArgs *)(uintptr_t)args.batch;   // read-only for the whole launch
+        const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+        int lo = 0, hi = args.n_batch - 1;   // wave-uniform
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (descs[mid].work_begin <= slot) lo = mid;
+            else hi = mid - 1;
+        }
+        ap = descs + lo;
+        const uint32_t total = gemm_work_items_device(ap->out_features, ap->N, PAIRED);
+        const uint32_t per_xcd = (total + 7u) / 8u;
+        const uint32_t local = slot - ap->work_begin;
+        idx = xcd * per_xcd + local;
+        if (local >= per_xcd || idx >= total) return;
+    }
+    ConstGemmArgs &a = *ap;
     const uint32_t n_tiles = (a.out_features + kTileN - 1) / kTileN;
-    if (!block_to_work(n_tiles, (uint32_t)a.N / kP, member, tile)) return;
+    if (!BATCH && !block_to_index(n_tiles * ((uint32_t)a.N / kP), idx)) return;
+    const uint32_t member = idx / n_tiles;
+    const uint32_t tile = idx - member * n_tiles;
 
     G g{a};
     g.lane = threadIdx.x & 63;
@@ -560,10 +591,14 @@ __global__ __launch_bounds__(256) void quantize_kernel(const uint16_t *__restric
 template <int MODE, int TM, bool PAIRED>
 void launch_one(const GemmArgs &a, hipStream_t s)
 {
-    const uint32_t n_tiles = (a.out_features + kTileN - 1) / kTileN;
-    const uint32_t total = n_tiles * ((uint32_t)a.N / (PAIRED ? 2u : 1u));
-    const unsigned blocks = ((total + 7u) / 8u) * 8u;
-    gemm_kernel<MODE, TM, PAIRED><<<blocks, kThreads, 0, s>>>(a);
+    if (a.batch) {
+        const unsigned blocks = a.work_begin * 8u;   // slots per XCD queue x 8 queues
+        gemm_kernel<MODE, TM, PAIRED, true><<<blocks, kThreads, 0, s>>>(a);
+    } else {
+        const uint32_t total = gemm_work_items(a.out_features, a.N, PAIRED);
+        const unsigned blocks = ((total + 7u) / 8u) * 8u;
+        gemm_kernel<MODE, TM, PAIRED, false><<<blocks, kThreads, 0, s>>>(a);
+    }
 }
 
 template <int MODE, bool PAIRED>
@@ -594,6 +629,11 @@ hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_
 // tokens the 64 accumulator registers per lane take the whole CU and the gain is lost, so longer
 // token counts regenerate the draw per member.
 bool gemm_pairs_supported(int32_t T) { return T <= 128; }
+
+uint32_t gemm_work_items(int32_t out_features, int32_t N, bool paired)
+{
+    return (uint32_t)((out_features + kTileN - 1) / kTileN) * ((uint32_t)N / (paired ? 2u : 1u));
+}
 
 hipError_t launch_gemm(const GemmArgs &a, int bits, int act_mode, bool paired, hipStream_t s)
 {

@@ -54,6 +54,12 @@ struct GemmArgs {
     int32_t qmin;
     uint32_t qspan;
     uint32_t tensor_id;
+    // batched launch: the kernel argument carries N, T and these three; each tensor's own GemmArgs
+    // (all fields above) sits in `batch`. Work is queued per XCD: a tensor with W work items
+    // occupies ceil(W/8) consecutive slots of every XCD's queue, starting at its work_begin.
+    const GemmArgs *batch;
+    int32_t n_batch;
+    uint32_t work_begin;         // per tensor: first slot; kernel argument: slots per XCD queue
 };
 
 hipError_t launch_noise_words(uint64_t seed, uint32_t tensor_id, uint64_t pair_begin, uint64_t n_pairs,
@@ -80,5 +86,7 @@ hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_
 // perturbed) and one workgroup evaluates both members from one draw; needs gemm_pairs_supported(T)
 bool gemm_pairs_supported(int32_t T);
 hipError_t launch_gemm(const GemmArgs &a, int bits, int act_mode, bool paired, hipStream_t s);
+// work items (tiles of 64 output rows x members, or x pairs) of one tensor
+uint32_t gemm_work_items(int32_t out_features, int32_t N, bool paired);
 
 }  // namespace qes
