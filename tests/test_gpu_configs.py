@@ -4,7 +4,7 @@ Configs 1 and 2 run their whole multi-iteration loop in lock step: each ABI call
 identical inputs, and the fitness vector computed from the GPU's GEMM outputs is fed to both the
 GPU update and the oracle update, so the weights stay bit-identical and the next iteration's GEMM
 is again compared on identical weights. Config 1 is checked in full; config 2 and the big configs
-(3, 4, 5: one full-size layer, real N, T and K, the launch configuration bench.py times) are checked
+(3, 4, 5: one full-size layer, real N, T and K, in the batched launches bench.py times) are checked
 on sampled output rows, which the counter-based noise makes exact: first row, last row and seeded
 random rows of every tensor.
 """
@@ -104,49 +104,62 @@ def test_lock_step_iterations(env, cfg_index, n_random_rows):
 
 @pytest.mark.parametrize("cfg_index", [3, 4, 5])
 def test_full_size_layer_sampled_rows(env, cfg_index):
-    """One full-size layer of the big configurations: every tensor shape with the real N, T and K."""
+    """One full-size layer of the big configurations in the launch configuration bench.py times:
+    every tensor shape with the real N, T and K, the layer's GEMMs in one batched call and its
+    updates in one batched call, checked on sampled rows of every tensor."""
     torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
     cfg = wl.CONFIGS[cfg_index]
     seeds = wl.make_seeds(cfg, cfg.K + 1)
     fits = np.stack([oracle.normalize_fitness(r) for r in wl.make_rewards(cfg, cfg.K + 1)])
-    xs = {}
+    ots, dts, rows = [], [], []
     for li, spec in enumerate(cfg.linears):
-        rows = wl.sample_rows(cfg, 0, li, 10)
         ot = oracle.Tensor(wl.make_qweight(cfg, 0, li), wl.make_scales(cfg, 0, li), spec.out_features,
                            spec.in_features, cfg.bits, cfg.group_size, cfg.qmin, cfg.qmax, cfg.tensor_id(0, li))
-        dt = u.device_tensor(ot)
-        if spec.x_key not in xs:
-            xs.clear()      # one activation tensor at a time: config 4's are hundreds of MB
-            xb = wl.make_activations(cfg, spec.x_key, spec.in_features)
-            xs[spec.x_key] = (xb, u.to_dev(xb).view(torch.bfloat16))
-        xb, xd = xs[spec.x_key]
-        nbytes = qes.gemm_workspace_bytes(dt, cfg.N, cfg.T, cfg.act_mode)
-        ws = torch.empty(nbytes, dtype=torch.uint8, device=u.DEV) if nbytes else None
-        # ---- GEMM, sampled output columns, all members and tokens
-        y = _gemm(env, cfg, dt, seeds[cfg.K], xd, ws)
-        ref = oracle.perturbed_qgemm(ot, seeds[cfg.K], cfg.sigma, xb, act_mode=cfg.act_mode, rows=rows)
+        ots.append(ot)
+        dts.append(u.device_tensor(ot))
+        rows.append(wl.sample_rows(cfg, 0, li, 10))
+    xs_host, xs_dev = {}, {}
+    for spec in cfg.linears:
+        if spec.x_key not in xs_host:
+            xs_host[spec.x_key] = wl.make_activations(cfg, spec.x_key, spec.in_features)
+            xs_dev[spec.x_key] = u.to_dev(xs_host[spec.x_key]).view(torch.bfloat16)
+    xs = [xs_dev[spec.x_key] for spec in cfg.linears]
+    ys = [torch.empty((cfg.N, cfg.T, spec.out_features), dtype=torch.bfloat16, device=u.DEV) for spec in cfg.linears]
+    # ---- the layer's GEMMs in one call; sampled output columns, all members and tokens
+    nbytes = qes.gemm_batch_workspace_bytes(dts, xs, cfg.N, cfg.T, cfg.act_mode)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=u.DEV) if nbytes else None
+    qes.perturbed_qgemm_batch(dts, seeds[cfg.K], cfg.sigma, xs, ys, act_mode=cfg.act_mode, workspace=ws)
+    for li, spec in enumerate(cfg.linears):
+        sel = torch.from_numpy(rows[li].astype(np.int64)).to(u.DEV)
+        got = ys[li].index_select(2, sel).view(torch.int16).cpu().numpy().view(np.uint16)
+        ref = oracle.perturbed_qgemm(ots[li], seeds[cfg.K], cfg.sigma, xs_host[spec.x_key], act_mode=cfg.act_mode,
+                                     rows=rows[li])[:, :, rows[li]]
         if cfg.act_mode == 1:
-            assert (y[:, :, rows] == ref[:, :, rows]).all(), spec.name
+            assert (got == ref).all(), spec.name
         else:
-            ok, worst = u.bf16_close(y[:, :, rows], ref[:, :, rows])
+            ok, worst = u.bf16_close(got, ref)
             assert ok, (spec.name, worst)
-        del ws
-        # ---- replayed residual, sampled rows (fp32, compared exactly)
+    del ws, ys, xs, xs_dev, xs_host
+    # ---- replayed residual per tensor, sampled rows (fp32, compared exactly)
+    for li, spec in enumerate(cfg.linears):
         res = torch.empty((spec.out_features, spec.in_features), dtype=torch.float32, device=u.DEV)
-        qes.replay_residual(dt, seeds[:cfg.K], fits[:cfg.K], cfg.N, cfg.sigma, cfg.alpha, cfg.gamma, res)
-        res_rows = res[torch.from_numpy(rows.astype(np.int64)).to(u.DEV)].cpu().numpy()
+        qes.replay_residual(dts[li], seeds[:cfg.K], fits[:cfg.K], cfg.N, cfg.sigma, cfg.alpha, cfg.gamma, res)
+        res_rows = res[torch.from_numpy(rows[li].astype(np.int64)).to(u.DEV)].cpu().numpy()
         del res
         ref_res = np.zeros((spec.out_features, spec.in_features), dtype=np.float32)
-        oracle.replay_residual(ot, seeds[:cfg.K], fits[:cfg.K], cfg.N, cfg.sigma, cfg.alpha, cfg.gamma, rows=rows,
-                               residual=ref_res)
-        assert (res_rows.view(np.uint32) == ref_res[rows].view(np.uint32)).all(), spec.name
-        # ---- update with the full window, sampled rows, bit-exact packed weights
-        qes.update(dt, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha, cfg.gamma)
-        oracle.update(ot, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha, cfg.gamma,
-                      rows=rows)
-        got = dt.qweight.cpu().numpy()
-        assert (_packed_rows(ot, got, rows) == _packed_rows(ot, ot.qweight, rows)).all(), spec.name
-        del dt, got, ot
+        oracle.replay_residual(ots[li], seeds[:cfg.K], fits[:cfg.K], cfg.N, cfg.sigma, cfg.alpha, cfg.gamma,
+                               rows=rows[li], residual=ref_res)
+        assert (res_rows.view(np.uint32) == ref_res[rows[li]].view(np.uint32)).all(), spec.name
+    # ---- the layer's updates in one call with the full window; sampled rows, bit-exact packed weights
+    stats = torch.zeros(2, dtype=torch.int64, device=u.DEV)
+    qes.update_batch(dts, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha, cfg.gamma,
+                     stats=stats)
+    for li, spec in enumerate(cfg.linears):
+        oracle.update(ots[li], seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha, cfg.gamma,
+                      rows=rows[li])
+        got = dts[li].qweight.cpu().numpy()
+        assert (_packed_rows(ots[li], got, rows[li]) == _packed_rows(ots[li], ots[li].qweight, rows[li])).all(), spec.name
+    assert int(stats[0]) > 0
 
 
 def test_maximum_population_and_history(env):
