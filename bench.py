@@ -22,7 +22,7 @@ sys.path.insert(0, ROOT)
 
 import workloads as wl  # noqa: E402
 
-# ---- roofline constants (derivations in the design doc) ----------------------------------------------
+# ---- roofline constants ---------------------------------------------------------------------------
 # Vector ALU peak: MI355X's published fp32 vector rate is 157.3 TFLOP/s = 256 CUs x 4 SIMDs x
 # 32 lanes x 2.4 GHz fused multiply-adds (2 flops each), i.e. 78.6e12 lane-operations per second.
 VALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12

@@ -49,11 +49,11 @@ __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
 // N1 + N2 for the tensor kernels: counter (pair, 0, tensor_id, 0) with a wave-uniform key and
 // tensor id. Same function as philox4x32_10(pair, 0, tensor_id, 0, k0, k1); written round by round
 // so that everything that does not depend on the lane is computed on the scalar unit (the second
-// product of round 1, the first product of round 2, the pre-xored round keys) and every
+// product of the first Philox round, the first product of the second, the pre-xored round keys) and every
 // three-input xor of lane data is a single instruction.
 __device__ __forceinline__ Words philox_tensor(uint32_t pair, uint32_t tensor_id, uint32_t k0, uint32_t k1)
 {
-    // round 1
+    // first Philox round
     uint64_t p0 = (uint64_t)kPhiloxM0 * (uint64_t)pair;
     const uint64_t u1 = (uint64_t)kPhiloxM1 * (uint64_t)tensor_id;           // uniform
     const uint32_t c0_1 = (uint32_t)(u1 >> 32) ^ k0;                          // uniform
@@ -62,7 +62,7 @@ __device__ __forceinline__ Words philox_tensor(uint32_t pair, uint32_t tensor_id
     uint32_t c3 = (uint32_t)p0;
     k0 += kPhiloxW0;
     k1 += kPhiloxW1;
-    // round 2
+    // second Philox round
     const uint64_t u0 = (uint64_t)kPhiloxM0 * (uint64_t)c0_1;                 // uniform
     uint64_t p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
     uint32_t c0 = (uint32_t)(p1 >> 32) ^ (c1_1 ^ k0);
@@ -71,14 +71,14 @@ __device__ __forceinline__ Words philox_tensor(uint32_t pair, uint32_t tensor_id
     const uint32_t c3_2 = (uint32_t)u0;                                       // uniform
     k0 += kPhiloxW0;
     k1 += kPhiloxW1;
-    // round 3
+    // third Philox round
     p0 = (uint64_t)kPhiloxM0 * (uint64_t)c0;
     p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
     c0 = xor3((uint32_t)(p1 >> 32), c1, k0);
     c2 = (uint32_t)(p0 >> 32) ^ (c3_2 ^ k1);
     c1 = (uint32_t)p1;
     c3 = (uint32_t)p0;
-    // rounds 4..10
+    // Philox rounds four to ten
 #pragma unroll
     for (int r = 3; r < 10; ++r) {
         k0 += kPhiloxW0;
