@@ -40,3 +40,29 @@ def test_product_does_not_import_the_oracle():
             if fn.endswith((".py", ".hip", ".hpp", ".h")):
                 src = open(os.path.join(dirpath, fn)).read()
                 assert "import oracle" not in src and "from oracle" not in src and "qes_oracle" not in src, fn
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    """No CPU fallback: a binding pointed at a missing library raises on first use."""
+    import importlib
+    import paper_2602_03120_amd.binding as b
+    fresh = importlib.reload(b)
+    try:
+        monkeypatch.setattr(fresh, "_LIB_PATH", str(tmp_path / "libqes.so"))
+        monkeypatch.setattr(fresh, "_lib", None)
+        try:
+            fresh.abi_version()
+        except ImportError as e:
+            assert "no fallback" in str(e)
+        else:
+            raise AssertionError("a missing library must raise")
+    finally:
+        importlib.reload(b)
