@@ -1,12 +1,13 @@
 """GPU parity on the benchmark configurations themselves (workloads.CONFIGS), through the C ABI.
 
 Configs 1 and 2 run their whole multi-iteration loop in lock step: each ABI call is compared on
-identical inputs, and the fitness vector computed from the GPU's GEMM outputs is fed to both the
-GPU update and the oracle update, so the weights stay bit-identical and the next iteration's GEMM
-is again compared on identical weights. Config 1 is checked in full; config 2 and the big configs
+identical inputs, and the fitness vector, computed from the ORACLE's GEMM outputs, is fed to both
+the GPU update and the oracle update, so the weights stay bit-identical and the next iteration's
+GEMM is again compared on identical weights. Nothing the GPU produced ever enters the oracle. Config 1 is checked in full; config 2 and the big configs
 (3, 4, 5: one full-size layer, real N, T and K, in the batched launches bench.py times) are checked
 on sampled output rows, which the counter-based noise makes exact: first row, last row and seeded
-random rows of every tensor.
+random rows of every tensor. The oracle follows only those rows (its copy of the other rows goes
+stale and is never read).
 """
 import numpy as np
 import pytest
@@ -79,11 +80,12 @@ def test_lock_step_iterations(env, cfg_index, n_random_rows):
             sel = slice(None) if rows[li] is None else rows[li]
             ok, worst = u.bf16_close(y[:, :, sel], ref[:, :, sel])
             assert ok, (it, spec.name, worst)
-            yf = wl.bf16_bits_to_f32(y).astype(np.float64)
-            mse += ((yf - targets[li][None]) ** 2).mean(axis=(1, 2))
-        # fitness = -MSE (mean over the layers), z-scored; taken from the GPU outputs for both sides
-        fit = qes.normalize_fitness((-mse / len(tensors)).astype(np.float32))
-        assert (fit == oracle.normalize_fitness((-mse / len(tensors)).astype(np.float32))).all()
+            rf = wl.bf16_bits_to_f32(ref[:, :, sel]).astype(np.float64)
+            mse += ((rf - targets[li][None][:, :, sel]) ** 2).mean(axis=(1, 2))
+        # fitness = -MSE over the columns the oracle evaluated (mean over the layers), z-scored;
+        # taken from the oracle's outputs for both sides
+        fit = oracle.normalize_fitness((-mse / len(tensors)).astype(np.float32))
+        assert (fit == qes.normalize_fitness((-mse / len(tensors)).astype(np.float32))).all()
         # ---- update with the history seen so far (window K), both sides
         lo = max(0, it - cfg.K)
         for li, (spec, ot, dt) in enumerate(tensors):
@@ -95,9 +97,6 @@ def test_lock_step_iterations(env, cfg_index, n_random_rows):
             sel = slice(None) if rows[li] is None else rows[li]
             assert (_packed_rows(ot, got, sel) == _packed_rows(ot, ot.qweight, sel)).all(), (it, spec.name)
             moved += int((_packed_rows(ot, ot.qweight, sel) != before).sum())
-            if rows[li] is not None:
-                # rows the oracle did not follow take the GPU's values, so the next GEMM sees identical weights
-                ot.qweight[...] = got.reshape(ot.qweight.shape)
         hist_fit = np.concatenate([hist_fit, fit[None]], axis=0)
     assert moved > 0
 
