@@ -135,8 +135,9 @@ int qes_perturbed_qgemm(const qes_tensor *w, const uint64_t *seeds, const uint8_
  * The same with antithetic perturbation pairs (App. A.1: "antithetic perturbation pairs"): N is
  * even, pair_seeds is HOST uint64 [N/2], members 2j and 2j+1 share pair_seeds[j], member 2j is
  * evaluated on Gate(W + δ_j) and member 2j+1 on Gate(W − δ_j). x, y and perturb_mask stay per
- * member. Up to 128 tokens per member one workgroup evaluates both members of a pair from a single
- * draw (half the noise work); longer token counts regenerate δ_j per member. Same results either way.
+ * member. Up to 128 tokens per member (256 in the batched call) one workgroup evaluates both
+ * members of a pair from a single draw (half the noise work); longer token counts regenerate δ_j
+ * per member. Same results either way.
  */
 int qes_perturbed_qgemm_antithetic(const qes_tensor *w, const uint64_t *pair_seeds, const uint8_t *perturb_mask,
                                    int32_t N, float sigma, const void *x, int32_t T, void *y, int32_t act_mode,

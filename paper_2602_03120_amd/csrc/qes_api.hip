@@ -427,7 +427,7 @@ static int gemm_common(const qes_tensor *w, const uint64_t *seeds, const uint8_t
     if (rc != QES_OK) return rc;
     // antithetic pairs share one draw inside a workgroup when both members' accumulators fit
     // and two workgroups still share a CU; longer token counts regenerate the draw per member
-    const bool paired = antithetic && qes::gemm_pairs_supported(T);
+    const bool paired = antithetic && qes::gemm_pairs_supported(T, false);
     const int32_t records = fill_gemm_entries((qes::Entry *)slot->host, seeds, perturb_mask, N, antithetic, paired);
     QES_HIP(hipMemcpyAsync(slot->dev, slot->host, (size_t)records * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
     a.entries = (const qes::Entry *)slot->dev;
@@ -505,7 +505,7 @@ static int gemm_batch_common(const qes_tensor *tensors, int32_t n_tensors, const
         }
     }
 
-    const bool paired = antithetic && qes::gemm_pairs_supported(T);
+    const bool paired = antithetic && qes::gemm_pairs_supported(T, true);
     const int32_t records = paired ? N / 2 : N;
     const size_t entry_bytes = (size_t)records * sizeof(qes::Entry);
     const size_t desc_bytes = (size_t)n_tensors * sizeof(qes::GemmArgs);

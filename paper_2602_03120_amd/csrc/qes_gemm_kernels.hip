@@ -607,8 +607,8 @@ hipError_t launch_mode(const GemmArgs &a, hipStream_t s)
     if (a.T <= 16) launch_one<MODE, 16, PAIRED>(a, s);
     else if (a.T <= 32) launch_one<MODE, 32, PAIRED>(a, s);
     else if (a.T <= 64) launch_one<MODE, 64, PAIRED>(a, s);
-    else if (a.T <= 128 || PAIRED) launch_one<MODE, 128, PAIRED>(a, s);
-    else if (a.T <= 256) launch_one<MODE, 256, false>(a, s);
+    else if (a.T <= 128) launch_one<MODE, 128, PAIRED>(a, s);
+    else if (a.T <= 256 || PAIRED) launch_one<MODE, 256, PAIRED>(a, s);
     else launch_one<MODE, 512, false>(a, s);
     return hipGetLastError();
 }
@@ -625,10 +625,12 @@ hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_
 }
 
 // A pair's workgroup holds the accumulators of both members. Up to 128 tokens per member that
-// leaves room for two workgroups per CU and the shared draw wins (1.4-1.6x per launch); at 256
-// tokens the 64 accumulator registers per lane take the whole CU and the gain is lost, so longer
-// token counts regenerate the draw per member.
-bool gemm_pairs_supported(int32_t T) { return T <= 128; }
+// leaves room for two workgroups per CU and the shared draw wins (1.4-1.6x per launch). At 256
+// tokens the 64 accumulator registers per lane take the whole CU: a single-tensor launch loses
+// more on its small tensors than it gains on the large ones, a launch over a whole layer still
+// gains (7 % on the 1.5B-model layer), so only batched launches pair up there. Longer token counts
+// regenerate the draw per member.
+bool gemm_pairs_supported(int32_t T, bool batched) { return T <= 128 || (batched && T <= 256); }
 
 uint32_t gemm_work_items(int32_t out_features, int32_t N, bool paired)
 {
@@ -638,7 +640,7 @@ uint32_t gemm_work_items(int32_t out_features, int32_t N, bool paired)
 hipError_t launch_gemm(const GemmArgs &a, int bits, int act_mode, bool paired, hipStream_t s)
 {
     if (paired) {
-        if (!gemm_pairs_supported(a.T) || (a.N & 1)) return hipErrorInvalidValue;
+        if (!gemm_pairs_supported(a.T, a.batch != nullptr) || (a.N & 1)) return hipErrorInvalidValue;
         if (act_mode == 1) return launch_mode<kI8W8, true>(a, s);
         return bits == 4 ? launch_mode<kBf16W4, true>(a, s) : launch_mode<kBf16W8, true>(a, s);
     }

@@ -83,8 +83,8 @@ hipError_t launch_quantize_activations(const void *x_bf16, int8_t *xq, float *x_
                                        int32_t in_features, hipStream_t s);
 // returns hipErrorInvalidValue when no kernel covers the request
 // paired: a.entries holds one record per antithetic pair (fit_bits bit 0 / bit 1: even / odd member
-// perturbed) and one workgroup evaluates both members from one draw; needs gemm_pairs_supported(T)
-bool gemm_pairs_supported(int32_t T);
+// perturbed) and one workgroup evaluates both members from one draw; needs gemm_pairs_supported()
+bool gemm_pairs_supported(int32_t T, bool batched);
 hipError_t launch_gemm(const GemmArgs &a, int bits, int act_mode, bool paired, hipStream_t s);
 // work items (tiles of 64 output rows x members, or x pairs) of one tensor
 uint32_t gemm_work_items(int32_t out_features, int32_t N, bool paired);

@@ -41,7 +41,8 @@ def _outputs(env, dts, N, T):
 
 
 @pytest.mark.parametrize("N,T,act,antithetic", [(6, 16, 0, False), (5, 64, 0, False), (3, 300, 0, False), (8, 100, 0, True),
-                                                (4, 200, 0, True), (6, 64, 1, False), (4, 40, 1, True)])
+                                                (4, 200, 0, True), (6, 64, 1, False), (4, 40, 1, True),
+                                                (6, 256, 0, True), (4, 256, 1, True), (2, 257, 0, True)])
 def test_batch_equals_single_calls_and_oracle(env, N, T, act, antithetic):
     torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
     if act == 0:
