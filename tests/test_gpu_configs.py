@@ -161,6 +161,42 @@ def test_full_size_layer_sampled_rows(env, cfg_index):
     assert int(stats[0]) > 0
 
 
+def test_every_layer_of_config_3_sampled_rows(env):
+    """All 28 layers (196 tensors, each with its own tensor id and weights) of the 1.5B-shaped
+    stack through the batched launches, four sampled rows per tensor: GEMM and update."""
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    cfg = wl.CONFIGS[3]
+    seeds = wl.make_seeds(cfg, cfg.K + 1)
+    fits = np.stack([oracle.normalize_fitness(r) for r in wl.make_rewards(cfg, cfg.K + 1)])
+    xs_host = {}
+    for spec in cfg.linears:
+        if spec.x_key not in xs_host:
+            xs_host[spec.x_key] = wl.make_activations(cfg, spec.x_key, spec.in_features)
+    xs_dev = {k: u.to_dev(v).view(torch.bfloat16) for k, v in xs_host.items()}
+    xs = [xs_dev[spec.x_key] for spec in cfg.linears]
+    ys = [torch.empty((cfg.N, cfg.T, spec.out_features), dtype=torch.bfloat16, device=u.DEV) for spec in cfg.linears]
+    for layer in range(cfg.n_layers):
+        ots = [oracle.Tensor(wl.make_qweight(cfg, layer, li), wl.make_scales(cfg, layer, li), spec.out_features,
+                             spec.in_features, cfg.bits, cfg.group_size, cfg.qmin, cfg.qmax, cfg.tensor_id(layer, li))
+               for li, spec in enumerate(cfg.linears)]
+        dts = [u.device_tensor(ot) for ot in ots]
+        rows = [wl.sample_rows(cfg, layer, li, 2) for li in range(len(cfg.linears))]
+        qes.perturbed_qgemm_batch(dts, seeds[cfg.K], cfg.sigma, xs, ys)
+        for li, spec in enumerate(cfg.linears):
+            sel = torch.from_numpy(rows[li].astype(np.int64)).to(u.DEV)
+            got = ys[li].index_select(2, sel).view(torch.int16).cpu().numpy().view(np.uint16)
+            ref = oracle.perturbed_qgemm(ots[li], seeds[cfg.K], cfg.sigma, xs_host[spec.x_key], rows=rows[li])
+            ok, worst = u.bf16_close(got, ref[:, :, rows[li]])
+            assert ok, (layer, spec.name, worst)
+        qes.update_batch(dts, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha, cfg.gamma)
+        for li, spec in enumerate(cfg.linears):
+            oracle.update(ots[li], seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha,
+                          cfg.gamma, rows=rows[li])
+            got = dts[li].qweight.cpu().numpy()
+            assert (_packed_rows(ots[li], got, rows[li]) == _packed_rows(ots[li], ots[li].qweight, rows[li])).all(), \
+                (layer, spec.name)
+
+
 def test_maximum_population_and_history(env):
     """N = 1024 members and hist_len = 256 generations (the ABI's limits) on a small tensor."""
     torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
