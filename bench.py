@@ -41,7 +41,8 @@ HBM_PEAK_GBPS = 8000.0
 # this file, scaled by the same counters on the plain copy issued below (see profiles/):
 # {(config, what one launch covers): bytes}: one layer's linears (qes_update_batch), or one tensor
 # with --per-tensor-update. A launch covers that much whatever --layers says.
-MEASURED_TRAFFIC_BYTES = {(2, "layer"): 6.79e6, (3, "layer"): 24.06e6, (2, "gate"): 2.374e6, (3, "gate"): 7.223e6}
+MEASURED_TRAFFIC_BYTES = {(2, "layer"): 6.79e6, (3, "layer"): 24.06e6, (4, "layer"): 47.46e6, (5, "layer"): 110.8e6,
+                          (2, "gate"): 2.374e6, (3, "gate"): 7.223e6}
 
 
 def parse():
