@@ -57,11 +57,11 @@ typedef __attribute__((address_space(1))) const void gbl_void;
 typedef const __attribute__((address_space(4))) GemmArgs ConstGemmArgs;
 
 constexpr int kRG = 4;          // row groups (of 16 output rows) per workgroup
-constexpr int kWaves = 8;       // waves per workgroup
-constexpr int kThreads = kWaves * 64;
 constexpr int kTileN = 16 * kRG;
-constexpr int kWM = 4;          // MFMA blocking: wave (wm, wr) owns token tiles m = wm mod 4 ...
-constexpr int kWR = 2;          // ... of row groups 2*wr and 2*wr+1
+// Waves per workgroup: 8, or 16 for the 512-token tile, whose 512 x 64 accumulators would not fit
+// the registers of 8 waves (64 per lane, plus fragments and noise) without spilling to memory.
+constexpr int waves_for(int tm) { return tm >= 512 ? 16 : 8; }
+constexpr int kWR = 2;          // MFMA blocking: wave (wm, wr) owns row groups 2*wr and 2*wr+1 ...
 constexpr int kRowBytes = 64;   // one LDS row of the activation tile: 32 bf16 or 64 int8
 constexpr int kFragBytes = kRG * 64 * 16;   // one buffer of B fragments: 16 bytes per lane and row group
 
@@ -153,18 +153,22 @@ struct Gemm {
     static constexpr int kSubK = kI8 ? 64 : 32;                // k extent of one substep
     static constexpr int kElemBytes = kI8 ? 1 : 2;             // activation element
     static constexpr int kMT = TM / 16;                        // token tiles per pass
+    static constexpr int kWaves = waves_for(TM);
+    static constexpr int kWM = kWaves / kWR;                   // ... and the token tiles m = wm (mod kWM)
+    static constexpr int kParts = kWaves / kRG;                // waves that share the noise of one row group's fragment
+    static constexpr int kPartBytes = 16 / kParts;             // bytes of a lane's fragment one wave generates
     static constexpr int kMy = (kMT + kWM - 1) / kWM;          // token tiles per wave
     static constexpr int kTileBytes = TM * kRowBytes;
     static constexpr int kInstr = TM / 16;                     // wave instructions per activation tile
     static constexpr int kMyInstr = (kInstr + kWaves - 1) / kWaves;
-    static constexpr int H = kI8 ? 8 : 4;                      // elements in this wave's half fragment
+    static constexpr int H = (kI8 ? 16 : 8) / kParts;          // elements in this wave's part of a fragment
     static constexpr int kWBytesPerSub = (MODE == kBf16W4) ? 16 : (MODE == kBf16W8 ? 32 : 64);   // weight bytes per row and substep
     using Acc = typename std::conditional<kI8, i32x4, f32x4>::type;
 
     ConstGemmArgs &a;
     Entry en;
     int lane, wave, wm, wr, ln, kc, n_sub;
-    int jrg, jhalf;               // noise job of this wave: half `jhalf` of row group `jrg`'s fragment
+    int jrg, jpart;               // noise job of this wave: part `jpart` of row group `jrg`'s fragment
     bool tail;                    // int8 only: in_features % 64 == 32, the last substep is half empty
     const uint16_t *scales[kWR];  // scale rows of this lane's two MFMA row groups
     const uint16_t *job_scales;   // scale row of this lane's noise job
@@ -225,44 +229,42 @@ struct Gemm {
         }
     }
 
-    // the packed base integers of this wave's half fragment of substep s (2, 4 or 8 bytes), fetched
-    // one substep before they are needed
+    // the packed base integers of this wave's part of the fragment of substep s (1 to 8 bytes),
+    // fetched one substep before they are needed
     __device__ __forceinline__ uint2 load_raw(int s) const
     {
+        constexpr int kBytes = (MODE == kBf16W4) ? H / 2 : H;
         const char *p = wrow_lane + (size_t)s * kWBytesPerSub;
         if (kI8 && tail && s == n_sub - 1 && kc >= 2) p -= 32;   // past the row: any valid address, value unused
-        if (MODE == kBf16W4) return make_uint2(*(const uint16_t *)p, 0u);
-        if (MODE == kBf16W8) return make_uint2(*(const uint32_t *)p, 0u);
+        if (kBytes == 1) return make_uint2(*(const uint8_t *)p, 0u);
+        if (kBytes == 2) return make_uint2(*(const uint16_t *)p, 0u);
+        if (kBytes == 4) return make_uint2(*(const uint32_t *)p, 0u);
         return *(const uint2 *)p;
     }
 
-    // this wave's half of a B fragment of substep s: draw, gate (Eq. 4), pack as exact small integers
+    // this wave's part of a B fragment of substep s: draw, gate (Eq. 4), pack as exact small integers
     struct Halves {
         uint2 d[kP];
     };
 
     __device__ __forceinline__ uint2 pack_half(const int32_t (&w)[H]) const
     {
-        if (kI8) return make_uint2(pack_i8x4(w[0], w[1], w[2], w[3]), pack_i8x4(w[H - 4], w[H - 3], w[H - 2], w[H - 1]));
-        return make_uint2(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]));
+        if (kI8) {
+            const uint32_t lo = pack_i8x4(w[0], w[1], w[2], w[3]);
+            return make_uint2(lo, H > 4 ? pack_i8x4(w[H - 4], w[H - 3], w[H - 2], w[H - 1]) : 0u);
+        }
+        const uint32_t lo = pack_bf16x2(w[0], w[1]);
+        return make_uint2(lo, H > 2 ? pack_bf16x2(w[H - 2], w[H - 1]) : 0u);
     }
 
     template <int PERTURB>
     __device__ __forceinline__ Halves make_half(int s, uint2 raw, bool zero) const
     {
         int32_t w[H];
-        if (MODE == kBf16W4) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) w[j] = ((int32_t)(raw.x << (28 - 4 * j))) >> 28;
-        } else if (MODE == kBf16W8) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) w[j] = ((int32_t)(raw.x << (24 - 8 * j))) >> 24;
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                w[j] = ((int32_t)(raw.x << (24 - 8 * j))) >> 24;
-                w[4 + j] = ((int32_t)(raw.y << (24 - 8 * j))) >> 24;
-            }
+        for (int j = 0; j < H; ++j) {
+            if (MODE == kBf16W4) w[j] = ((int32_t)(raw.x << (28 - 4 * j))) >> 28;
+            else w[j] = ((int32_t)((j < 4 ? raw.x : raw.y) << (24 - 8 * (j & 3)))) >> 24;
         }
         Halves out;
         const uint32_t pair = pair0 + (uint32_t)s * (kSubK / 2);
@@ -301,7 +303,11 @@ struct Gemm {
     __device__ __forceinline__ void publish(int buffer, const Halves &hv)
     {
 #pragma unroll
-        for (int h = 0; h < kP; ++h) *(uint2 *)(bfrag + (buffer * kP + h) * kFragBytes + frag_wr) = hv.d[h];
+        for (int h = 0; h < kP; ++h) {
+            char *dst = bfrag + (buffer * kP + h) * kFragBytes + frag_wr;
+            if (kPartBytes == 8) *(uint2 *)dst = hv.d[h];
+            else *(uint32_t *)dst = hv.d[h].x;
+        }
     }
 
     // scales of group g+1, requested when group g opens so that nothing waits for them
@@ -463,7 +469,7 @@ struct Gemm {
 // a block finds its tensor by bisection over the tensors' first slots in the per-XCD queues.
 // Register budget: two workgroups per CU (4 waves per SIMD) also for the largest accumulator sets.
 template <int MODE, int TM, bool PAIRED, bool BATCH>
-__global__ __launch_bounds__(kThreads, ((!PAIRED && TM >= 512) || (PAIRED && TM == 128) ? 4 : 1)) void gemm_kernel(const GemmArgs args)
+__global__ __launch_bounds__(waves_for(TM) * 64, ((!PAIRED && TM >= 512) || (PAIRED && TM == 128) ? 4 : 1)) void gemm_kernel(const GemmArgs args)
 {
     using G = Gemm<MODE, TM, PAIRED>;
     constexpr int kP = G::kP;
@@ -505,10 +511,10 @@ __global__ __launch_bounds__(kThreads, ((!PAIRED && TM >= 512) || (PAIRED && TM 
     G g{a};
     g.lane = threadIdx.x & 63;
     g.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    g.wm = g.wave % kWM;
-    g.wr = g.wave / kWM;
-    g.jrg = g.wave >> 1;
-    g.jhalf = g.wave & 1;
+    g.wm = g.wave % G::kWM;
+    g.wr = g.wave / G::kWM;
+    g.jrg = g.wave / G::kParts;
+    g.jpart = g.wave % G::kParts;
     g.ln = g.lane & 15;        // column of B / C within a row group
     g.kc = g.lane >> 4;        // k-chunk 0..3
     const int n0 = tile * kTileN;
@@ -536,14 +542,14 @@ __global__ __launch_bounds__(kThreads, ((!PAIRED && TM >= 512) || (PAIRED && TM 
         yg[h] = (uint16_t *)a.y + m * a.T * a.out_features;
         xs[h] = G::kI8 ? a.x_scale + m * a.T : nullptr;
     }
-    // noise job: half `jhalf` of row group jrg: elements k0 .. k0+H-1, k0 = s*kSubK + kc*(kSubK/4) + jhalf*H
+    // noise job: part `jpart` of row group jrg's fragment: elements k0 .. k0+H-1, k0 = s*kSubK + kc*(kSubK/4) + jpart*H
     const int jn = clamp_row(n0 + g.jrg * 16 + g.ln);
-    const int k0 = g.kc * (G::kSubK / 4) + g.jhalf * G::H;
+    const int k0 = g.kc * (G::kSubK / 4) + g.jpart * G::H;
     const size_t elem0 = (size_t)jn * a.in_features + k0;
     g.job_scales = (const uint16_t *)a.scales + (size_t)jn * groups_per_row;
     g.wrow_lane = (const char *)a.qweight + (MODE == kBf16W4 ? (elem0 >> 1) : elem0);
     g.pair0 = (uint32_t)(elem0 >> 1);
-    g.frag_wr = g.jrg * 1024 + g.lane * 16 + g.jhalf * 8;
+    g.frag_wr = g.jrg * 1024 + g.lane * 16 + g.jpart * G::kPartBytes;
     g.a_off = (g.wm * 16 + g.ln) * kRowBytes + swizzle(g.ln, g.kc) * 16;
     g.bfrag = bfrag;
     // per member: 0 base weights, 1 +δ, 2 -δ (antithetic mirror); per pair: bit 0 = even member
@@ -593,11 +599,11 @@ void launch_one(const GemmArgs &a, hipStream_t s)
 {
     if (a.batch) {
         const unsigned blocks = a.work_begin * 8u;   // slots per XCD queue x 8 queues
-        gemm_kernel<MODE, TM, PAIRED, true><<<blocks, kThreads, 0, s>>>(a);
+        gemm_kernel<MODE, TM, PAIRED, true><<<blocks, waves_for(TM) * 64, 0, s>>>(a);
     } else {
         const uint32_t total = gemm_work_items(a.out_features, a.N, PAIRED);
         const unsigned blocks = ((total + 7u) / 8u) * 8u;
-        gemm_kernel<MODE, TM, PAIRED, false><<<blocks, kThreads, 0, s>>>(a);
+        gemm_kernel<MODE, TM, PAIRED, false><<<blocks, waves_for(TM) * 64, 0, s>>>(a);
     }
 }
 
