@@ -8,14 +8,15 @@
 // exactly once and that the noise arithmetic is spread evenly over all waves, with the MFMAs, the
 // LDS traffic and the global loads hidden underneath it.
 //
-// Decomposition. A workgroup (8 waves) owns one member, 4 groups of 16 output rows and ALL tokens
-// of that member (TM per pass). Per k-substep (32 k for bf16, 64 k for int8 operands) the MFMA B
-// fragment of a row group is 4 dwords per lane; each wave regenerates one half of one row group's
-// fragment (two or four Philox pairs per lane: draw, gate against the base integers, pack as exact
-// small-integer bf16 or int8), publishes it through LDS, and after the workgroup barrier wave
-// (wm, wr) reads the fragments of row groups 2 wr and 2 wr + 1 back (one b128 each) and runs the
-// MFMAs of the token tiles m = wm (mod 4). So the noise work per wave is an eighth of the
-// workgroup's whatever the token count, and short token counts still use all waves for noise.
+// Decomposition. A workgroup (8 waves, 16 for the 512-token tile) owns one member, 4 groups of 16
+// output rows and ALL tokens of that member (TM per pass). Per k-substep (32 k for bf16, 64 k for
+// int8 operands) the MFMA B fragment of a row group is 4 dwords per lane; the waves split the four
+// fragments evenly (a half or a quarter of one each: one to four Philox pairs per lane: draw, gate
+// against the base integers, pack as exact small-integer bf16 or int8), publish them through LDS,
+// and after the workgroup barrier wave (wm, wr) reads the fragments of row groups 2 wr and 2 wr + 1
+// back (one b128 each) and runs the MFMAs of the token tiles m = wm (mod 4 or 8). So the noise work
+// per wave is an equal share of the workgroup's whatever the token count, and short token counts
+// still use all waves for noise.
 //
 // Antithetic pairs (PAIRED). Members 2j and 2j+1 use +δ and -δ of one draw, so a workgroup owns the
 // pair: every draw is generated once, gated twice (W+δ for the even member, W-δ for the odd one),
