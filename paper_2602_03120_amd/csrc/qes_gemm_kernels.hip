@@ -59,9 +59,9 @@ typedef const __attribute__((address_space(4))) GemmArgs ConstGemmArgs;
 
 constexpr int kRG = 4;          // row groups (of 16 output rows) per workgroup
 constexpr int kTileN = 16 * kRG;
-// Waves per workgroup: 8, or 16 for the 512-token tile, whose 512 x 64 accumulators would not fit
-// the registers of 8 waves (64 per lane, plus fragments and noise) without spilling to memory.
-constexpr int waves_for(int tm) { return tm >= 512 ? 16 : 8; }
+// Waves per workgroup: 8, or 16 where 8 waves would hold 64 accumulator registers per lane (the
+// 512-token tile; a pair of members at 256 tokens), which spills or leaves two waves per SIMD.
+constexpr int waves_for(int tm, bool paired) { return (tm >= 512 || (paired && tm >= 256)) ? 16 : 8; }
 constexpr int kWR = 2;          // MFMA blocking: wave (wm, wr) owns row groups 2*wr and 2*wr+1 ...
 constexpr int kRowBytes = 64;   // one LDS row of the activation tile: 32 bf16 or 64 int8
 constexpr int kFragBytes = kRG * 64 * 16;   // one buffer of B fragments: 16 bytes per lane and row group
@@ -154,7 +154,7 @@ struct Gemm {
     static constexpr int kSubK = kI8 ? 64 : 32;                // k extent of one substep
     static constexpr int kElemBytes = kI8 ? 1 : 2;             // activation element
     static constexpr int kMT = TM / 16;                        // token tiles per pass
-    static constexpr int kWaves = waves_for(TM);
+    static constexpr int kWaves = waves_for(TM, PAIRED);
     static constexpr int kWM = kWaves / kWR;                   // ... and the token tiles m = wm (mod kWM)
     static constexpr int kParts = kWaves / kRG;                // waves that share the noise of one row group's fragment
     static constexpr int kPartBytes = 16 / kParts;             // bytes of a lane's fragment one wave generates
@@ -470,7 +470,7 @@ struct Gemm {
 // a block finds its tensor by bisection over the tensors' first slots in the per-XCD queues.
 // Register budget: two workgroups per CU (4 waves per SIMD) also for the largest accumulator sets.
 template <int MODE, int TM, bool PAIRED, bool BATCH>
-__global__ __launch_bounds__(waves_for(TM) * 64, ((!PAIRED && TM >= 512) || (PAIRED && TM == 128) ? 4 : 1)) void gemm_kernel(const GemmArgs args)
+__global__ __launch_bounds__(waves_for(TM, PAIRED) * 64, ((TM >= 512 || (PAIRED && TM >= 128)) ? 4 : 1)) void gemm_kernel(const GemmArgs args)
 {
     using G = Gemm<MODE, TM, PAIRED>;
     constexpr int kP = G::kP;
@@ -600,11 +600,11 @@ void launch_one(const GemmArgs &a, hipStream_t s)
 {
     if (a.batch) {
         const unsigned blocks = a.work_begin * 8u;   // slots per XCD queue x 8 queues
-        gemm_kernel<MODE, TM, PAIRED, true><<<blocks, waves_for(TM) * 64, 0, s>>>(a);
+        gemm_kernel<MODE, TM, PAIRED, true><<<blocks, waves_for(TM, PAIRED) * 64, 0, s>>>(a);
     } else {
         const uint32_t total = gemm_work_items(a.out_features, a.N, PAIRED);
         const unsigned blocks = ((total + 7u) / 8u) * 8u;
-        gemm_kernel<MODE, TM, PAIRED, false><<<blocks, waves_for(TM) * 64, 0, s>>>(a);
+        gemm_kernel<MODE, TM, PAIRED, false><<<blocks, waves_for(TM, PAIRED) * 64, 0, s>>>(a);
     }
 }
 
