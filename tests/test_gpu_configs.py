@@ -197,6 +197,39 @@ def test_every_layer_of_config_3_sampled_rows(env):
                 (layer, spec.name)
 
 
+def test_largest_tensor_indexing(env):
+    """A tensor just under the ABI's 2^33-element limit (4.3 GB of packed INT4, 2^32 - 2^20 pairs):
+    element offsets need 64 bits and pair indices all 32. GEMM, replay and update on the first, the
+    last and random rows; the oracle follows only those rows."""
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    out_f, in_f = 65536, 131040
+    assert out_f * in_f < 2 ** 33 and out_f * in_f // 2 > 2 ** 32 - 2 ** 21
+    rng = np.random.default_rng(77)
+    qw = rng.integers(0, 256, size=(out_f, in_f // 2), dtype=np.uint8)
+    sc = wl.f16_bits(rng.uniform(0.005, 0.02, size=(out_f, in_f // 32)).astype(np.float32))
+    ot = oracle.Tensor(qw, sc, out_f, in_f, 4, 32, -8, 7, 4000000000)          # a tensor id above 2^31 as well
+    dt = qes.Tensor(torch.from_numpy(qw).to(u.DEV), u.to_dev(sc), out_f, in_f, 4, 32, -8, 7, 4000000000)
+    rows = np.unique(np.concatenate([[0, 1, out_f - 1, 32768, 32769], rng.integers(0, out_f, size=4)])).astype(np.int32)
+    sel = torch.from_numpy(rows.astype(np.int64)).to(u.DEV)
+    N, T, K = 2, 16, 1
+    seeds = rng.integers(0, 2 ** 64, size=(K + 1, N), dtype=np.uint64)
+    fit = np.float32([[1.0, -1.0], [-1.0, 1.0]])
+    x = wl.f32_to_bf16_bits(rng.standard_normal((N, T, in_f)).astype(np.float32))
+    y = torch.empty((N, T, out_f), dtype=torch.bfloat16, device=u.DEV)
+    qes.perturbed_qgemm(dt, seeds[K], 1.0, u.to_dev(x).view(torch.bfloat16), y)
+    got = y.index_select(2, sel).view(torch.int16).cpu().numpy().view(np.uint16)
+    ref = oracle.perturbed_qgemm(ot, seeds[K], 1.0, x, rows=rows)[:, :, rows]
+    ok, worst = u.bf16_close(got, ref)
+    assert ok, worst
+    stats = torch.zeros(2, dtype=torch.int64, device=u.DEV)
+    before = qw[rows].copy()                      # the oracle updates qw in place
+    qes.update(dt, seeds[K], fit[K], seeds[:K], fit[:K], 1.0, 2.0, 0.9, stats=stats)
+    oracle.update(ot, seeds[K], fit[K], seeds[:K], fit[:K], 1.0, 2.0, 0.9, rows=rows)
+    got_rows = dt.qweight.view(out_f, in_f // 2).index_select(0, sel).cpu().numpy()
+    assert (got_rows == ot.qweight[rows]).all()
+    assert int(stats[0]) > 2 ** 32 and (got_rows != before).any()      # the counters are 64-bit too
+
+
 def test_maximum_population_and_history(env):
     """N = 1024 members and hist_len = 256 generations (the ABI's limits) on a small tensor."""
     torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
