@@ -142,3 +142,28 @@ def test_update_argument_errors(env):
         qes.update(dt, seeds, bad, None, None, 1.0, 0.5, 0.9)
     torch.cuda.synchronize()
     assert (dt.qweight == before).all()
+
+
+def test_many_calls_with_changing_record_sizes(env):
+    """Back-to-back updates without host synchronisation whose (seed, fitness) record blocks shrink
+    and grow (4 members without history up to 512 members with 64 generations): the library's
+    staging slots are reused and regrown underneath; the final weights are the oracle's."""
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    qw, _, qmin, qmax = wl.random_tensor(321, 64, 128, 4, 0)
+    ot = oracle.Tensor(qw, None, 64, 128, 4, 0, qmin, qmax, 8)
+    dt = u.device_tensor(ot)
+    rng = np.random.default_rng(99)
+    plan = [(4, 0), (8, 3), (30, 8), (512, 64), (6, 1), (64, 32), (5, 0), (16, 16), (1024, 2), (7, 7)] * 3
+    calls = []
+    for N, K in plan:
+        seeds = rng.integers(0, 2 ** 64, size=(K + 1, N), dtype=np.uint64)
+        fit = np.stack([oracle.normalize_fitness(rng.standard_normal(N).astype(np.float32)) for _ in range(K + 1)])
+        calls.append((seeds, fit, K))
+    stats = torch.zeros(2, dtype=torch.int64, device=u.DEV)
+    for seeds, fit, K in calls:                       # all enqueued before anything is checked
+        qes.update(dt, seeds[K], fit[K], seeds[:K], fit[:K], 1.0, 1.5, 0.9, stats=stats)
+    ref_stats = np.zeros(2, dtype=np.uint64)
+    for seeds, fit, K in calls:
+        ref_stats = oracle.update(ot, seeds[K], fit[K], seeds[:K], fit[:K], 1.0, 1.5, 0.9, stats=ref_stats)
+    assert (dt.qweight.cpu().numpy() == ot.qweight).all()
+    assert (stats.cpu().numpy().view(np.uint64) == ref_stats).all() and ref_stats[0] > 100
