@@ -6,7 +6,13 @@ of workloads.CONFIGS: the perturbed quantised GEMM of every linear layer for eve
 (population evaluation), then the seeded update with a full replay window for every tensor.
 Inputs are resident in HBM before the timed region starts. Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--no-cpu-baseline] [--no-extras]
+    python bench.py --split-phase        (replay on a side stream during evaluation; its own JSON line)
+
+The headline workload is config 5 (the 8B-shaped stack of App. C: 32 layers, 6.98 G parameters,
+N=32, T=128, K=32), the largest configuration that runs on one GPU. After the timed steps the same
+run measures, outside the timed region: the machine ceilings with the library's own probes, the
+replay-only and Full-Residual entry points, and two steps of the smaller configurations.
 """
 import argparse
 import dataclasses
@@ -37,12 +43,13 @@ OPS_PER_EF_STEP = 11.0                 # Eq. 6-8 + gate, per element and generat
 OPS_PER_MEMBER_ELEMENT_GEMM = 6.0      # Eq. 4 gate and the exact small-integer operand packing
 MFMA_PEAK = {"bf16": 2.5e15, "i8": 5.0e15}
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this file, scaled by the same counters on the plain copy issued below (see profiles/):
-# {(config, what one launch covers): bytes}: one layer's linears (qes_update_batch), or one tensor
-# with --per-tensor-update. A launch covers that much whatever --layers says.
-MEASURED_TRAFFIC_BYTES = {(2, "layer"): 6.79e6, (3, "layer"): 24.06e6, (4, "layer"): 47.46e6, (5, "layer"): 110.8e6,
-                          (2, "gate"): 2.374e6, (3, "gate"): 7.223e6}
+# Counter figures of the dominant kernel's launch (qes_update_batch over one layer's linears), from
+# the rocprofv3 --pmc runs of this file summarised under profiles/. They hold for exactly the
+# (config, N, K) they were measured on and are omitted for anything else.
+#   traffic_bytes: FETCH_SIZE + WRITE_SIZE per launch, scaled by the same counters on the plain
+#                  copy issued below;  valu_insts: SQ_INSTS_VALU (wave instructions) per launch.
+MEASURED_PER_LAUNCH = {}
+HEADLINE_CONFIG = 5
 
 
 def parse():
@@ -50,7 +57,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=2, choices=sorted(wl.CONFIGS))
+    ap.add_argument("--config", type=int, default=HEADLINE_CONFIG, choices=sorted(wl.CONFIGS))
     ap.add_argument("--layers", type=int, default=None, help="limit the number of layers (debug)")
     ap.add_argument("--K", type=int, default=None, help="override the replay window of the configuration")
     ap.add_argument("--N", type=int, default=None, help="override the population of the configuration")
@@ -59,13 +66,276 @@ def parse():
     ap.add_argument("--per-tensor-update", action="store_true",
                     help="one qes_update call per tensor instead of one qes_update_batch call per layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip what runs after the timed steps: ceilings, replay-only and Full-Residual timings, "
+                         "the two-step runs of the smaller configurations")
     ap.add_argument("--antithetic", action="store_true",
                     help="members come in +δ/-δ pairs sharing a seed (App. A.1); not the headline setting")
+    ap.add_argument("--split-phase", action="store_true",
+                    help="time one layer with the replay on a side stream next to the evaluation, then one Alg. 1 "
+                         "step, against the single-call step (§4.6, App. E.2); prints its own JSON line")
     return ap.parse_args()
 
 
 def update_ops_per_element(N, generations):
     return generations * (N * (OPS_PER_PAIR_DRAW / 2 + OPS_PER_MEMBER_ELEMENT_UPDATE) + OPS_PER_EF_STEP)
+
+
+class Workload:
+    """A configuration's tensors, activations and output buffers, resident in device memory."""
+
+    def __init__(self, torch, qes, cfg, n_layers, dev):
+        self.cfg, self.n_layers = cfg, n_layers
+        self.layer_tensors = []
+        for layer in range(n_layers):
+            row = []
+            for li, spec in enumerate(cfg.linears):
+                qw = torch.from_numpy(wl.make_qweight(cfg, layer, li)).to(dev)
+                sc = torch.from_numpy(wl.make_scales(cfg, layer, li).view(np.float16)).to(dev)
+                row.append(qes.Tensor(qw, sc, spec.out_features, spec.in_features, cfg.bits, cfg.group_size,
+                                      cfg.qmin, cfg.qmax, cfg.tensor_id(layer, li)))
+            self.layer_tensors.append(row)
+        xs = {}
+        for spec in cfg.linears:
+            if spec.x_key not in xs:
+                xb = wl.make_activations(cfg, spec.x_key, spec.in_features)
+                xs[spec.x_key] = torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16)
+        self.layer_xs = [xs[spec.x_key] for spec in cfg.linears]
+        # a batched launch writes all outputs of a layer at once: one buffer per linear, reused by every layer
+        self.layer_ys = [torch.empty((cfg.N, cfg.T, spec.out_features), dtype=torch.bfloat16, device=dev)
+                         for spec in cfg.linears]
+        ws_bytes = max(max(qes.gemm_workspace_bytes(t, cfg.N, cfg.T, cfg.act_mode) for t in self.layer_tensors[0]),
+                       qes.gemm_batch_workspace_bytes(self.layer_tensors[0], self.layer_xs, cfg.N, cfg.T, cfg.act_mode))
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
+        self.stats = torch.zeros(2, dtype=torch.int64, device=dev)
+        self.params = n_layers * sum(l.out_features * l.in_features for l in cfg.linears)
+
+
+def run_steps(torch, qes, work, steps, warmup, anti=False, per_tensor_gemm=False, per_tensor_update=False):
+    """warmup untimed steps, then `steps` timed ones bracketed by synchronisations. Returns the wall
+    time per step and the HIP-event times (recorded on the launch stream) of the evaluation pass
+    and of every update launch."""
+    cfg, n_layers = work.cfg, work.n_layers
+    total_steps = steps + warmup
+    seeds = wl.make_seeds(cfg, cfg.K + total_steps, cfg.N // 2 if anti else cfg.N)
+    fits = np.stack([qes.normalize_fitness(r) for r in wl.make_rewards(cfg, cfg.K + total_steps)])
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    gemm_events, upd_events = [], []
+
+    def step(s, timed):
+        # population evaluation: every linear, every member
+        g0, g1 = ev(), ev()
+        g0.record()
+        for layer in range(n_layers):
+            if per_tensor_gemm:
+                for li, t in enumerate(work.layer_tensors[layer]):
+                    qes.perturbed_qgemm(t, seeds[cfg.K + s], cfg.sigma, work.layer_xs[li], work.layer_ys[li],
+                                        act_mode=cfg.act_mode, workspace=work.ws, antithetic=anti)
+            else:
+                # the linears of a layer share members and token count: one launch per layer
+                qes.perturbed_qgemm_batch(work.layer_tensors[layer], seeds[cfg.K + s], cfg.sigma, work.layer_xs,
+                                          work.layer_ys, act_mode=cfg.act_mode, workspace=work.ws, antithetic=anti)
+        g1.record()
+        # seeded update with a full replay window (steady state: K generations of history): all
+        # linears of a layer share the generation's records and go in one call
+        h0 = s
+        for layer in range(n_layers):
+            if per_tensor_update:
+                for li, t in enumerate(work.layer_tensors[layer]):
+                    u0, u1 = ev(), ev()
+                    u0.record()
+                    qes.update(t, seeds[cfg.K + s], fits[cfg.K + s], seeds[h0:h0 + cfg.K], fits[h0:h0 + cfg.K],
+                               cfg.sigma, cfg.alpha, cfg.gamma, stats=work.stats, antithetic=anti)
+                    u1.record()
+                    if timed:
+                        upd_events.append((li, u0, u1))
+            else:
+                u0, u1 = ev(), ev()
+                u0.record()
+                qes.update_batch(work.layer_tensors[layer], seeds[cfg.K + s], fits[cfg.K + s], seeds[h0:h0 + cfg.K],
+                                 fits[h0:h0 + cfg.K], cfg.sigma, cfg.alpha, cfg.gamma, stats=work.stats, antithetic=anti)
+                u1.record()
+                if timed:
+                    upd_events.append((-1, u0, u1))
+        if timed:
+            gemm_events.append((g0, g1))
+
+    for s in range(warmup):
+        step(s, False)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for s in range(warmup, total_steps):
+        step(s, True)
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    upd_ms_by_li = {}
+    for li, a, b in upd_events:
+        upd_ms_by_li.setdefault(li, []).append(a.elapsed_time(b))
+    return {"ms_per_step": (t_end - t_begin) * 1e3 / steps,
+            "gemm_ms": float(np.mean([a.elapsed_time(b) for a, b in gemm_events])),
+            "upd_ms_by_li": {k: float(np.mean(v)) for k, v in upd_ms_by_li.items()}}
+
+
+def part_figures(cfg, work, r, anti, per_tensor_update):
+    """GEMM-only and update-only rates of a run, with the fractions of the MFMA, HBM and VALU peaks."""
+    member_tokens = cfg.N * cfg.T
+    mfma_dtype = "i8" if cfg.act_mode == 1 else "bf16"
+    params = work.params
+    draws_n = cfg.N // 2 if anti else cfg.N
+    if per_tensor_update:
+        upd_ms_total = float(sum(r["upd_ms_by_li"].values())) * work.n_layers
+    else:
+        upd_ms_total = r["upd_ms_by_li"][-1] * work.n_layers
+    upd_gbps = params * (cfg.bits / 8.0 * 2.0) / (upd_ms_total * 1e-3) / 1e9      # packed W read + written
+    upd_draws = params * (cfg.K + 1) * draws_n
+    upd_ops = params * update_ops_per_element(draws_n, cfg.K + 1)
+    gemm_s = r["gemm_ms"] * 1e-3
+    return {
+        "gemm_ms_per_pass": r["gemm_ms"],
+        "gemm_member_tokens_per_s": member_tokens / gemm_s,
+        "gemm_mfma_frac": 2.0 * params * member_tokens / gemm_s / MFMA_PEAK[mfma_dtype],
+        "gemm_mfma_dtype": mfma_dtype,
+        "gemm_draws_per_s": params * draws_n / gemm_s,
+        "gemm_alu_frac": params * draws_n * (OPS_PER_PAIR_DRAW / 2 + OPS_PER_MEMBER_ELEMENT_GEMM) / gemm_s / 1e12
+        / VALU_PEAK_TOPS,
+        "update_ms_per_step": upd_ms_total,
+        "update_gb_per_s": upd_gbps,
+        "update_hbm_frac": upd_gbps / HBM_PEAK_GBPS,
+        "update_draws_per_s": upd_draws / (upd_ms_total * 1e-3),
+        "update_alu_frac": upd_ops / (upd_ms_total * 1e-3) / 1e12 / VALU_PEAK_TOPS,
+    }
+
+
+def time_call(torch, fn, reps, warm=1):
+    """Mean HIP-event time in ms of fn() over reps calls on the current stream."""
+    for _ in range(warm):
+        fn()
+    pairs = []
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+
+
+def measure_ceilings(torch, qes, dev):
+    """What the machine sustains on each resource, measured with the library's own probe kernels in
+    this run: Philox words/s and full pair draws/s (four chains per thread, eight waves per SIMD, no
+    memory), bf16 and int8 matrix instructions on register operands, a plain streaming copy."""
+    out = {}
+    n_threads = 256 * 4 * 8 * 64 * 4          # 4 rounds of 8 waves per SIMD
+    sink = torch.empty(n_threads, dtype=torch.int32, device=dev)
+    iters = 512
+    ms = time_call(torch, lambda: qes.bench_noise(0, n_threads, iters, 1.0, sink), 5)
+    out["philox_words_per_s"] = 4.0 * n_threads * iters / (ms * 1e-3)
+    ms = time_call(torch, lambda: qes.bench_noise(1, n_threads, iters, 1.0, sink), 5)
+    out["pair_draws_per_s"] = n_threads * iters / (ms * 1e-3)
+    out["draws_per_s"] = 2.0 * out["pair_draws_per_s"]
+    n_blocks, m_iters, tiles = 256 * 8, 4096, 8
+    msink = torch.empty(n_blocks * 256, dtype=torch.int32, device=dev)
+    ms = time_call(torch, lambda: qes.bench_mfma(0, n_blocks, m_iters, msink), 5)
+    out["mfma_bf16_flop_per_s"] = n_blocks * 4.0 * m_iters * tiles * 16384.0 / (ms * 1e-3)
+    ms = time_call(torch, lambda: qes.bench_mfma(1, n_blocks, m_iters, msink), 5)
+    out["mfma_i8_op_per_s"] = n_blocks * 4.0 * m_iters * tiles * 32768.0 / (ms * 1e-3)
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    ms = time_call(torch, lambda: qes.bench_copy(src, dst, nbytes), 10, warm=2)
+    out["copy_gb_per_s"] = 2.0 * nbytes / (ms * 1e-3) / 1e9          # read + written
+    return out
+
+
+def measure_update_variants(torch, qes, work, dev):
+    """Entry points of the update family that the timed step does not call: the replay loop alone
+    (qes_replay_residual, every tensor of layer 0) and single Alg. 1 steps on a stored residual
+    (qes_update_full_residual, fp32 and binary16, the largest tensor; at the configured population and
+    at N=2, where the step is closest to memory-bound)."""
+    cfg = work.cfg
+    seeds = wl.make_seeds(cfg, cfg.K + 1)
+    fits = np.stack([qes.normalize_fitness(r) for r in wl.make_rewards(cfg, cfg.K + 1)])
+    tensors = work.layer_tensors[0]
+    big = max(tensors, key=lambda t: t.out_features * t.in_features)
+    res = torch.zeros((big.out_features, big.in_features), dtype=torch.float32, device=dev)
+    out = {}
+    replay_ms = 0.0
+    for t in tensors:
+        view = res.view(-1)[: t.out_features * t.in_features].view(t.out_features, t.in_features)
+        replay_ms += time_call(torch, lambda: qes.replay_residual(t, seeds[:cfg.K], fits[:cfg.K], cfg.N, cfg.sigma,
+                                                                  cfg.alpha, cfg.gamma, view), 2)
+    layer_elems = sum(t.out_features * t.in_features for t in tensors)
+    out["replay_residual_ms_per_layer"] = replay_ms
+    out["replay_residual_ms_per_step_est"] = replay_ms * cfg.n_layers
+    out["replay_residual_draws_per_s"] = layer_elems * cfg.K * cfg.N / (replay_ms * 1e-3)
+    # fp32 residual written: 4 bytes per element next to half a byte (INT4) or one byte (INT8) read
+    out["replay_residual_gb_per_s"] = layer_elems * (cfg.bits / 8.0 + 4.0) / (replay_ms * 1e-3) / 1e9
+    elems = big.out_features * big.in_features
+    res16 = torch.zeros((big.out_features, big.in_features), dtype=torch.float16, device=dev)
+    for name, state, half, e_bytes in (("f32", res, False, 8.0), ("f16", res16, True, 4.0)):
+        for n_pop in sorted({cfg.N, 2}):
+            state.zero_()
+            ms = time_call(torch, lambda: qes.update_full_residual(big, seeds[cfg.K][:n_pop], fits[cfg.K][:n_pop],
+                                                                   cfg.sigma, cfg.alpha, cfg.gamma, state, half=half), 10,
+                           warm=2)
+            gbps = elems * (cfg.bits / 8.0 * 2.0 + e_bytes) / (ms * 1e-3) / 1e9
+            out["full_residual_%s_N%d" % (name, n_pop)] = {
+                "tensor": "%dx%d" % (big.out_features, big.in_features), "ms": ms,
+                "draws_per_s": elems * n_pop / (ms * 1e-3), "gb_per_s": gbps, "hbm_frac": gbps / HBM_PEAK_GBPS}
+    return out
+
+
+def split_phase(torch, qes, dev, cfg_index=3, reps=5):
+    """One layer, two ways (§4.6, App. E.2: replay off the critical path). Single call: evaluation,
+    then qes_update_batch (replay + step). Split: qes_replay_residual of every tensor on a side
+    stream while the evaluation runs on the main stream, then one Alg. 1 step per tensor
+    (qes_update_full_residual) on the replayed residual. Both produce the same weights."""
+    cfg = wl.CONFIGS[cfg_index]
+    work = Workload(torch, qes, cfg, 1, dev)
+    seeds = wl.make_seeds(cfg, cfg.K + 1)
+    fits = np.stack([qes.normalize_fitness(r) for r in wl.make_rewards(cfg, cfg.K + 1)])
+    tensors = work.layer_tensors[0]
+    residuals = [torch.empty((t.out_features, t.in_features), dtype=torch.float32, device=dev) for t in tensors]
+    side = torch.cuda.Stream()
+
+    def evaluate():
+        qes.perturbed_qgemm_batch(tensors, seeds[cfg.K], cfg.sigma, work.layer_xs, work.layer_ys, act_mode=cfg.act_mode,
+                                  workspace=work.ws)
+
+    def single():
+        evaluate()
+        qes.update_batch(tensors, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha, cfg.gamma)
+
+    def split():
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for t, r in zip(tensors, residuals):
+                qes.replay_residual(t, seeds[:cfg.K], fits[:cfg.K], cfg.N, cfg.sigma, cfg.alpha, cfg.gamma, r)
+        evaluate()
+        torch.cuda.current_stream().wait_stream(side)
+        for t, r in zip(tensors, residuals):
+            qes.update_full_residual(t, seeds[cfg.K], fits[cfg.K], cfg.sigma, cfg.alpha, cfg.gamma, r)
+
+    def after_rollout():
+        for t, r in zip(tensors, residuals):
+            qes.update_full_residual(t, seeds[cfg.K], fits[cfg.K], cfg.sigma, cfg.alpha, cfg.gamma, r)
+
+    def wall(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    out = {"workload": "config %d, one layer (%s), N=%d, T=%d, K=%d" % (cfg.index, "/".join(l.name for l in cfg.linears),
+                                                                      cfg.N, cfg.T, cfg.K),
+           "evaluation_ms": wall(evaluate), "single_call_step_ms": wall(single), "split_phase_step_ms": wall(split),
+           "work_after_last_rollout_single_ms": None, "work_after_last_rollout_split_ms": wall(after_rollout)}
+    out["work_after_last_rollout_single_ms"] = out["single_call_step_ms"] - out["evaluation_ms"]
+    return out
 
 
 def main():
@@ -81,7 +351,11 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dev = "cuda:0"
+    if args.split_phase:
+        print(json.dumps({"metric": "split-phase step time", "unit": "ms", "n_gpus": 1, **split_phase(torch, qes, dev)}))
+        return
     cfg = wl.CONFIGS[args.config]
+    overridden = args.K is not None or args.N is not None or args.layers is not None
     if args.K is not None or args.N is not None:
         # the replay window is a cost knob (§4.6, App. E.2: cost linear in K); not the headline setting
         cfg = dataclasses.replace(cfg, K=cfg.K if args.K is None else args.K, N=cfg.N if args.N is None else args.N)
@@ -90,30 +364,14 @@ def main():
             sys.exit(2)
     n_layers = cfg.n_layers if args.layers is None else min(args.layers, cfg.n_layers)
     big = cfg.params > 100_000_000
-    steps = args.steps if args.steps is not None else (2 if big else 20)
+    steps = args.steps if args.steps is not None else (3 if big else 20)
     warmup = args.warmup if args.warmup is not None else (1 if big else 3)
+    anti = args.antithetic
+    if anti and cfg.N % 2:
+        print("bench.py: --antithetic needs an even population", file=sys.stderr)
+        sys.exit(2)
 
-    # ---------------- inputs, resident in HBM
-    tensors = []   # (layer, li, qes.Tensor)
-    for layer in range(n_layers):
-        for li, spec in enumerate(cfg.linears):
-            qw = torch.from_numpy(wl.make_qweight(cfg, layer, li)).to(dev)
-            sc = torch.from_numpy(wl.make_scales(cfg, layer, li).view(np.float16)).to(dev)
-            tensors.append((layer, li, qes.Tensor(qw, sc, spec.out_features, spec.in_features, cfg.bits,
-                                                  cfg.group_size, cfg.qmin, cfg.qmax, cfg.tensor_id(layer, li))))
-    xs = {}
-    for spec in cfg.linears:
-        if spec.x_key not in xs:
-            xb = wl.make_activations(cfg, spec.x_key, spec.in_features)
-            xs[spec.x_key] = torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16)
-    layer_tensors = [[t for la, _, t in tensors if la == layer] for layer in range(n_layers)]
-    layer_xs = [xs[spec.x_key] for spec in cfg.linears]
-    # a batched launch writes all outputs of a layer at once: one buffer per linear
-    layer_ys = [torch.empty((cfg.N, cfg.T, spec.out_features), dtype=torch.bfloat16, device=dev) for spec in cfg.linears]
-    ws_bytes = max(max(qes.gemm_workspace_bytes(t, cfg.N, cfg.T, cfg.act_mode) for _, _, t in tensors),
-                   qes.gemm_batch_workspace_bytes(layer_tensors[0], layer_xs, cfg.N, cfg.T, cfg.act_mode))
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
-    stats = torch.zeros(2, dtype=torch.int64, device=dev)
+    work = Workload(torch, qes, cfg, n_layers, dev)
     # one plain copy of known size before the timed region: the reference dispatch that scales the
     # rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the same run
     copy_bytes = 256 << 20
@@ -123,99 +381,48 @@ def main():
     torch.cuda.synchronize()
     del copy_src, copy_dst
 
-    total_steps = steps + warmup
-    anti = args.antithetic
-    if anti and cfg.N % 2:
-        print("bench.py: --antithetic needs an even population", file=sys.stderr)
-        sys.exit(2)
-    seeds = wl.make_seeds(cfg, cfg.K + total_steps, cfg.N // 2 if anti else cfg.N)
-    rewards = wl.make_rewards(cfg, cfg.K + total_steps)
-    fits = np.stack([qes.normalize_fitness(r) for r in rewards])
-
-    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
-    gemm_events, upd_events = [], []
-
-    def step(s, timed):
-        # population evaluation: every linear, every member
-        g0, g1 = ev(), ev()
-        g0.record()
-        if args.per_tensor_gemm:
-            for layer, li, t in tensors:
-                spec = cfg.linears[li]
-                qes.perturbed_qgemm(t, seeds[cfg.K + s], cfg.sigma, xs[spec.x_key], layer_ys[li],
-                                    act_mode=cfg.act_mode, workspace=ws, antithetic=anti)
-        else:
-            # the linears of a layer share members and token count: one launch per layer
-            for layer in range(n_layers):
-                qes.perturbed_qgemm_batch(layer_tensors[layer], seeds[cfg.K + s], cfg.sigma, layer_xs, layer_ys,
-                                          act_mode=cfg.act_mode, workspace=ws, antithetic=anti)
-        g1.record()
-        # seeded update with a full replay window (steady state: K generations of history): all
-        # linears of a layer share the generation's records and go in one call
-        h0 = s
-        if args.per_tensor_update:
-            for layer, li, t in tensors:
-                u0, u1 = ev(), ev()
-                u0.record()
-                qes.update(t, seeds[cfg.K + s], fits[cfg.K + s], seeds[h0:h0 + cfg.K], fits[h0:h0 + cfg.K],
-                           cfg.sigma, cfg.alpha, cfg.gamma, stats=stats, antithetic=anti)
-                u1.record()
-                if timed:
-                    upd_events.append((li, u0, u1))
-        else:
-            for layer in range(n_layers):
-                u0, u1 = ev(), ev()
-                u0.record()
-                qes.update_batch(layer_tensors[layer], seeds[cfg.K + s], fits[cfg.K + s], seeds[h0:h0 + cfg.K],
-                                 fits[h0:h0 + cfg.K], cfg.sigma, cfg.alpha, cfg.gamma, stats=stats, antithetic=anti)
-                u1.record()
-                if timed:
-                    upd_events.append((-1, u0, u1))
-        if timed:
-            gemm_events.append((g0, g1))
-
-    for s in range(warmup):
-        step(s, False)
-    torch.cuda.synchronize()
-    t_begin = time.perf_counter()
-    for s in range(warmup, total_steps):
-        step(s, True)
-    torch.cuda.synchronize()
-    t_end = time.perf_counter()
-
-    ms_per_step = (t_end - t_begin) * 1e3 / steps
+    r = run_steps(torch, qes, work, steps, warmup, anti, args.per_tensor_gemm, args.per_tensor_update)
+    ms_per_step = r["ms_per_step"]
     member_tokens = cfg.N * cfg.T
     value = member_tokens / (ms_per_step * 1e-3)
+    parts = part_figures(cfg, work, r, anti, args.per_tensor_update)
+    parts["weights_changed_total"] = int(work.stats[0].item())
+    parts["gated_total"] = int(work.stats[1].item())
 
-    # ---------------- per-part figures from HIP events recorded on the launch stream
-    gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in gemm_events]))
-    params = n_layers * sum(l.out_features * l.in_features for l in cfg.linears)
-    mfma_dtype = "i8" if cfg.act_mode == 1 else "bf16"
-    gemm_flops = 2.0 * params * member_tokens
-    upd_ms_by_li = {}
-    for li, a, b in upd_events:
-        upd_ms_by_li.setdefault(li, []).append(a.elapsed_time(b))
     # dominant kernel: the update. One launch = one layer's linears (qes_update_batch), or, with
     # --per-tensor-update, the largest tensor shape (most launches x longest)
+    draws_n = cfg.N // 2 if anti else cfg.N
     if args.per_tensor_update:
         dom_li = max(range(len(cfg.linears)), key=lambda i: cfg.linears[i].out_features * cfg.linears[i].in_features)
         dom = cfg.linears[dom_li]
-        dom_ms = float(np.mean(upd_ms_by_li[dom_li]))
+        dom_ms = r["upd_ms_by_li"][dom_li]
         dom_elems = dom.out_features * dom.in_features
         dom_name = "update_kernel (qes_update, %s %dx%d)" % (dom.name, dom.out_features, dom.in_features)
-        traffic_key = (cfg.index, dom.name)
-        upd_ms_total = float(sum(np.mean(v) for v in upd_ms_by_li.values())) * n_layers
+        counters = None
     else:
-        dom_ms = float(np.mean(upd_ms_by_li[-1]))
+        dom_ms = r["upd_ms_by_li"][-1]
         dom_elems = sum(l.out_features * l.in_features for l in cfg.linears)
         dom_name = "update_kernel (qes_update_batch, one layer: %s)" % "+".join(l.name for l in cfg.linears)
-        traffic_key = (cfg.index, "layer")
-        upd_ms_total = dom_ms * n_layers
-    ops = dom_elems * update_ops_per_element(cfg.N // 2 if anti else cfg.N, cfg.K + 1)
+        counters = None if anti else MEASURED_PER_LAUNCH.get((cfg.index, cfg.N, cfg.K))
+    ops = dom_elems * update_ops_per_element(draws_n, cfg.K + 1)
     achieved_tops = ops / (dom_ms * 1e-3) / 1e12
-    bytes_per_param = cfg.bits / 8.0 * 2.0          # packed W read + written
-    upd_gbps = params * bytes_per_param / (upd_ms_total * 1e-3) / 1e9
-    upd_draws = params * (cfg.K + 1) * (cfg.N // 2 if anti else cfg.N)
+    roofline = {
+        "kernel": dom_name,
+        "bound": "alu", "achieved": achieved_tops, "peak": VALU_PEAK_TOPS, "unit": "Tlane-op/s",
+        "frac": achieved_tops / VALU_PEAK_TOPS,
+        "traffic": counters["traffic_bytes"] if counters else None,
+        "traffic_source": "static: rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE summary under profiles/ for this config, N and K"
+        if counters else None,
+        "avg_launch_ms": dom_ms,
+        "algorithmic_ops_per_launch": ops,
+        "algorithmic_ops_per_pair_draw": OPS_PER_PAIR_DRAW,
+        "algorithmic_bytes_per_launch": dom_elems * cfg.bits / 8.0 * 2.0,
+        # issued vector instructions (SQ_INSTS_VALU, 64 lanes each) against the same peak: what the
+        # compiled kernel actually occupies the VALUs with, as opposed to the hand count above
+        "issue_frac": counters["valu_insts"] * 64.0 / (dom_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS if counters else None,
+        "valu_insts_per_pair_draw": counters["valu_insts"] / (dom_elems / 2.0 * (cfg.K + 1) * draws_n) if counters else None,
+        "draws_per_s": dom_elems * (cfg.K + 1) * draws_n / (dom_ms * 1e-3),
+    }
 
     out = {
         "metric": "member-tokens/s",
@@ -228,38 +435,43 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int32+f32 noise/update; %s MFMA" % mfma_dtype,
+        "dtype": "int32+f32 noise/update; %s MFMA" % parts["gemm_mfma_dtype"],
         "data": "synthetic",
         "config": {"workload": "config %d: %s (%d layers of %s), N=%d, T=%d, K=%d, sigma=%g, alpha=%g, gamma=%g"
                    % (cfg.index, cfg.name, n_layers, "/".join(l.name for l in cfg.linears), cfg.N, cfg.T, cfg.K,
                       cfg.sigma, cfg.alpha, cfg.gamma),
-                   "parameters": params, "step": "perturbed qGEMM of every linear + update with full replay window; %s"
+                   "parameters": work.params, "step": "perturbed qGEMM of every linear + update with full replay window; %s"
                    % ("GEMM: one call per %s, update: one call per %s"
                       % ("tensor" if args.per_tensor_gemm else "layer", "tensor" if args.per_tensor_update else "layer")),
-                   "antithetic_pairs": bool(anti)},
-        "roofline": {
-            "kernel": dom_name,
-            "bound": "alu", "achieved": achieved_tops, "peak": VALU_PEAK_TOPS, "unit": "Tlane-op/s",
-            "frac": achieved_tops / VALU_PEAK_TOPS,
-            "traffic": None if anti else MEASURED_TRAFFIC_BYTES.get(traffic_key),
-            "avg_launch_ms": dom_ms,
-            "algorithmic_ops_per_launch": ops,
-            "algorithmic_bytes_per_launch": dom_elems * cfg.bits / 8.0 * 2.0,
-        },
-        "parts": {
-            "gemm_ms_per_pass": gemm_ms,
-            "gemm_member_tokens_per_s": member_tokens / (gemm_ms * 1e-3),
-            "gemm_mfma_frac": gemm_flops / (gemm_ms * 1e-3) / MFMA_PEAK[mfma_dtype],
-            "gemm_draws_per_s": params * cfg.N / (gemm_ms * 1e-3),
-            "gemm_alu_frac": params * cfg.N * (OPS_PER_PAIR_DRAW / 2 + OPS_PER_MEMBER_ELEMENT_GEMM)
-            / (gemm_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS,
-            "update_ms_per_step": upd_ms_total,
-            "update_gb_per_s": upd_gbps,
-            "update_hbm_frac": upd_gbps / HBM_PEAK_GBPS,
-            "update_draws_per_s": upd_draws / (upd_ms_total * 1e-3),
-            "weights_changed_total": int(stats[0].item()), "gated_total": int(stats[1].item()),
-        },
+                   "antithetic_pairs": bool(anti), "overridden": bool(overridden)},
+        "roofline": roofline,
+        "parts": parts,
     }
+
+    if not args.no_extras:
+        ceilings = measure_ceilings(torch, qes, dev)
+        out["ceilings"] = ceilings
+        # the binding resource, against what the same generator sustains with nothing else to do
+        roofline["frac_of_measured_noise_ceiling"] = roofline["draws_per_s"] / ceilings["draws_per_s"]
+        parts["gemm_frac_of_measured_noise_ceiling"] = parts["gemm_draws_per_s"] / ceilings["draws_per_s"]
+        parts.update(measure_update_variants(torch, qes, work, dev))
+        if not overridden and not anti and cfg.index == HEADLINE_CONFIG:
+            del work
+            torch.cuda.empty_cache()
+            others = {}
+            for index in (2, 3, 4):
+                c = wl.CONFIGS[index]
+                w2 = Workload(torch, qes, c, c.n_layers, dev)
+                r2 = run_steps(torch, qes, w2, 2, 1)
+                p2 = part_figures(c, w2, r2, False, False)
+                p2["ms_per_step"] = r2["ms_per_step"]
+                p2["member_tokens_per_s"] = c.N * c.T / (r2["ms_per_step"] * 1e-3)
+                p2["workload"] = "config %d: %s, %d layers, N=%d, T=%d, K=%d; 2 steps after 1 warm-up" % (
+                    c.index, c.name, c.n_layers, c.N, c.T, c.K)
+                others[str(index)] = p2
+                del w2
+                torch.cuda.empty_cache()
+            parts["configs"] = others
 
     if not args.no_cpu_baseline and not anti:
         out["cpu_baseline"] = cpu_baseline(cfg, member_tokens)
@@ -268,8 +480,9 @@ def main():
 
 def cpu_baseline(cfg, member_tokens):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the same
-    workload: a fixed stride of output rows of every tensor of layer 0, all members, tokens and
-    generations. Reported in the metric's unit by scaling the sample's time to the whole step."""
+    workload: evenly spaced output rows of every tensor of layer 0 (the same share of each tensor),
+    all members, tokens and generations. Reported in the metric's unit by scaling the sample's time
+    to the whole step."""
     import oracle
     cores = len(os.sched_getaffinity(0))
     omp = os.environ.get("OMP_NUM_THREADS")
@@ -277,17 +490,18 @@ def cpu_baseline(cfg, member_tokens):
         cores = min(cores, int(omp))
     # aim at roughly 8e9 draws of work in the sample (10-20 s on 16 cores)
     layer_params = sum(l.out_features * l.in_features for l in cfg.linears)
-    step_draws = layer_params * cfg.n_layers * cfg.N * (cfg.K + 2)
-    stride = max(1, int(round(step_draws / 8.0e9)))
+    step_draws = float(layer_params) * cfg.n_layers * cfg.N * (cfg.K + 2)
+    share = min(1.0, 8.0e9 / step_draws * cfg.n_layers)          # of layer 0's rows
     seeds = wl.make_seeds(cfg, cfg.K + 1)
     fits = np.stack([oracle.normalize_fitness(r) for r in wl.make_rewards(cfg, cfg.K + 1)])
     xs = {}
-    sample_rows_total = 0
+    sample_elems = 0
     t0 = time.perf_counter()
     t_prep = 0.0
     for li, spec in enumerate(cfg.linears):
         p0 = time.perf_counter()
-        rows = np.arange(0, spec.out_features, stride * cfg.n_layers, dtype=np.int32)
+        n_rows = max(1, int(round(spec.out_features * share)))
+        rows = np.unique(np.linspace(0, spec.out_features - 1, n_rows).astype(np.int32))
         w = oracle.Tensor(wl.make_qweight(cfg, 0, li), wl.make_scales(cfg, 0, li), spec.out_features,
                           spec.in_features, cfg.bits, cfg.group_size, cfg.qmin, cfg.qmax, cfg.tensor_id(0, li))
         if spec.x_key not in xs:
@@ -296,14 +510,14 @@ def cpu_baseline(cfg, member_tokens):
         oracle.perturbed_qgemm(w, seeds[cfg.K], cfg.sigma, xs[spec.x_key], act_mode=cfg.act_mode, rows=rows)
         oracle.update(w, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha, cfg.gamma,
                       rows=rows)
-        sample_rows_total += rows.size * spec.in_features
+        sample_elems += rows.size * spec.in_features
     elapsed = time.perf_counter() - t0 - t_prep
-    frac = sample_rows_total / float(layer_params * cfg.n_layers)
+    frac = sample_elems / float(layer_params * cfg.n_layers)
     est_step_s = elapsed / frac
     return {"value": member_tokens / est_step_s, "unit": "member-tokens/s", "cores": cores, "kind": "oracle",
-            "sample": "every %d-th output row of each tensor of layer 0 (%.4g of the step's elements), all members, "
-                      "tokens and generations; %.1f s of oracle time scaled to the whole step"
-                      % (stride * cfg.n_layers, frac, elapsed)}
+            "sample": "%.3g of the output rows of each tensor of layer 0, evenly spaced (%.3g of the step's elements), "
+                      "all members, tokens and generations: GEMM and update; %.1f s of oracle time scaled to the whole step"
+                      % (share, frac, elapsed)}
 
 
 if __name__ == "__main__":

@@ -7,8 +7,21 @@
  * without waiting for it. Small HOST arrays (seeds, fitnesses) are copied before the call
  * returns, so the caller may reuse them immediately.
  *
- * Every entry point returns QES_OK (0) or a negative qes_status; nothing throws. On error no
- * device work has been enqueued.
+ * Every entry point returns QES_OK (0) or a negative qes_status; nothing throws. Every check
+ * that can refuse a call (arguments, limits, workspace) is made before any device work is enqueued:
+ * a call that returns QES_ERR_INVALID_ARG, QES_ERR_UNSUPPORTED or QES_ERR_WORKSPACE has touched no
+ * device memory. QES_ERR_HIP reports a failing runtime call and
+ * may leave earlier launches of the same call on the stream.
+ *
+ * Device memory the library owns. Entry points that take HOST arrays of seeds and fitnesses stage
+ * them through a ring of 8 slot pairs (pinned host + device, about 4.6 MB each: room for
+ * QES_MAX_HISTORY + 1 generations of QES_MAX_POPULATION records plus QES_MAX_BATCH descriptors).
+ * The ring is allocated by the first such call on a device (hipHostMalloc / hipMalloc, once) and
+ * kept until the process ends; no later call allocates or frees. A slot is reused once an event
+ * recorded behind its last consumer has completed, so with more than 8 calls outstanding the host
+ * waits for the oldest (not while holding the library's lock: callers on other streams go on).
+ * Because of the first-call allocation and the copy from the pinned slot, these entry points are
+ * not for use under stream capture.
  *
  * Passages of the paper each operation implements are cited at its declaration:
  *   §3.2 Eq. 3  stochastically rounded integer perturbation δ
@@ -280,12 +293,21 @@ int qes_normalize_fitness(const float *reward, int32_t N, float *fit);
 /* ---- machine ceilings measured with the library's own noise code (benchmark support) ---- */
 
 /*
- * Runs `iters` Philox calls (mode 0) or full pair draws (mode 1: Philox + Box-Muller + two
- * stochastic roundings) per thread on `n_threads` threads and xors the results into
- * sink[n_threads] (DEVICE uint32) so the work cannot be elided. No memory traffic in the loop.
+ * Noise ceiling. Runs `iters` (a multiple of 4) Philox calls (mode 0) or full pair draws (mode 1:
+ * Philox + Box-Muller + two stochastic roundings) per thread on `n_threads` threads, four
+ * independent chains at a time and eight waves per SIMD, the shape the update kernel runs the
+ * generator in, and folds the results into sink[n_threads] (DEVICE uint32) so the work cannot be
+ * elided. No memory traffic in the loop.
  */
 int qes_bench_noise(int32_t mode, uint64_t n_threads, int32_t iters, float sigma, uint32_t *sink,
                     void *stream);
+
+/*
+ * MFMA ceiling. Every wave of n_blocks workgroups (4 waves each) issues iters x 8 independent
+ * matrix instructions on register operands: mode 0 v_mfma_f32_16x16x32_bf16 (16384 flop each),
+ * mode 1 v_mfma_i32_16x16x64_i8 (32768 op each). sink: DEVICE uint32 [n_blocks * 256].
+ */
+int qes_bench_mfma(int32_t mode, uint32_t n_blocks, int32_t iters, uint32_t *sink, void *stream);
 
 /* Plain streaming copy of n_bytes (multiple of 16) from src to dst, both DEVICE, 16-byte aligned. */
 int qes_bench_copy(const void *src, void *dst, size_t n_bytes, void *stream);

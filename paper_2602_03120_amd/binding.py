@@ -72,6 +72,7 @@ def _load():
         "qes_update_stochastic_rounding": ([tp, vp, vp, i32, f32, f32, u64, vp, vp], i32),
         "qes_normalize_fitness": ([vp, i32, vp], i32),
         "qes_bench_noise": ([i32, u64, i32, f32, vp, vp], i32),
+        "qes_bench_mfma": ([i32, u32, i32, vp, vp], i32),
         "qes_bench_copy": ([vp, vp, sz, vp], i32),
         "qes_status_string": ([i32], ctypes.c_char_p),
         "qes_last_hip_error": ([], i32),
@@ -91,7 +92,7 @@ EXPORTS = ["qes_noise_words", "qes_noise_gauss", "qes_noise_delta", "qes_noise_f
            "qes_update_batch", "qes_update_batch_antithetic",
            "qes_replay_residual", "qes_replay_residual_antithetic", "qes_update_full_residual", "qes_update_full_residual_f16",
            "qes_update_stochastic_rounding", "qes_normalize_fitness",
-           "qes_bench_noise", "qes_bench_copy", "qes_status_string", "qes_last_hip_error",
+           "qes_bench_noise", "qes_bench_mfma", "qes_bench_copy", "qes_status_string", "qes_last_hip_error",
            "qes_abi_version"]
 
 
@@ -321,6 +322,10 @@ def normalize_fitness(reward):
 def bench_noise(mode, n_threads, iters, sigma, sink, stream=None):
     _check(_load().qes_bench_noise(mode, n_threads, iters, sigma, _dev_ptr(sink, "sink"), _stream(stream)),
            "qes_bench_noise")
+
+
+def bench_mfma(mode, n_blocks, iters, sink, stream=None):
+    _check(_load().qes_bench_mfma(mode, n_blocks, iters, _dev_ptr(sink, "sink"), _stream(stream)), "qes_bench_mfma")
 
 
 def bench_copy(src, dst, n_bytes, stream=None):

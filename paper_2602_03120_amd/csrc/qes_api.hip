@@ -2,6 +2,7 @@
 // arrays (seeds, fitnesses) into device memory in stream order, kernel launches.
 #include <algorithm>
 #include <cmath>
+#include <condition_variable>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -27,53 +28,109 @@ int hip_fail(hipError_t e)
     } while (0)
 
 // ---- staging ring: host arrays -> pinned slot -> device slot, ordered on the caller's stream.
-// A slot is reused only after the event recorded behind its last consumer has completed.
+// Every slot is large enough for the largest request the ABI accepts (records of
+// QES_MAX_HISTORY + 1 generations of QES_MAX_POPULATION members plus QES_MAX_BATCH descriptors), so
+// the ring is allocated once, on the first staging call on a device, and nothing is allocated or
+// freed on the call path afterwards. A slot is reused only after the event recorded behind its
+// last consumer has completed. The mutex guards slot bookkeeping only: filling a slot, the copy,
+// the launches and any wait for a slot's event happen outside it, so callers on different streams
+// do not serialise behind each other.
 constexpr int kSlots = 8;
 constexpr int kMaxDevices = 16;
+constexpr size_t kMaxDescBytes = sizeof(qes::GemmArgs) > sizeof(qes::TensorDesc) ? sizeof(qes::GemmArgs) : sizeof(qes::TensorDesc);
+constexpr size_t kSlotBytes =
+    (((size_t)(QES_MAX_HISTORY + 1) * QES_MAX_POPULATION * sizeof(qes::Entry) + (size_t)QES_MAX_BATCH * kMaxDescBytes) + 4095u) &
+    ~(size_t)4095u;
 
 struct Slot {
     void *host = nullptr;
     void *dev = nullptr;
-    size_t cap = 0;
     hipEvent_t ev = nullptr;
-    bool in_flight = false;
+    bool in_flight = false;   // an event behind the slot's last consumer has been recorded
+    bool held = false;        // a host thread is filling it
 };
 
 struct DeviceCtx {
+    bool ready = false;
     Slot slots[kSlots];
     int next = 0;
 };
 
 std::mutex g_mu;
+std::condition_variable g_cv;
 DeviceCtx g_ctx[kMaxDevices];
 
-// Returns a slot holding `bytes` of capacity, safe to overwrite. Caller holds g_mu.
+int init_ring(DeviceCtx &c)   // caller holds g_mu; first staging call on this device only
+{
+    for (int i = 0; i < kSlots; ++i) {
+        Slot &s = c.slots[i];
+        if (!s.host) QES_HIP(hipHostMalloc(&s.host, kSlotBytes, hipHostMallocDefault));
+        if (!s.dev) QES_HIP(hipMalloc(&s.dev, kSlotBytes));
+        if (!s.ev) QES_HIP(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
+    }
+    c.ready = true;
+    return QES_OK;
+}
+
+// A slot the calling thread may fill: taken round-robin among the slots no other thread is
+// filling; if its last consumer is still running, waits for it (outside the mutex).
 int acquire_slot(size_t bytes, Slot **out)
 {
+    if (bytes > kSlotBytes) return QES_ERR_INVALID_ARG;   // cannot happen for arguments within the ABI limits
     int dev = 0;
     QES_HIP(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices) return QES_ERR_UNSUPPORTED;
     DeviceCtx &c = g_ctx[dev];
-    Slot &s = c.slots[c.next];
-    c.next = (c.next + 1) % kSlots;
-    if (!s.ev) QES_HIP(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
-    if (s.in_flight) {
-        QES_HIP(hipEventSynchronize(s.ev));
-        s.in_flight = false;
+    Slot *s = nullptr;
+    {
+        std::unique_lock<std::mutex> lock(g_mu);
+        if (!c.ready) {
+            const int rc = init_ring(c);
+            if (rc != QES_OK) return rc;
+        }
+        for (;;) {
+            for (int i = 0; i < kSlots && !s; ++i) {
+                Slot &cand = c.slots[(c.next + i) % kSlots];
+                if (!cand.held) {
+                    s = &cand;
+                    c.next = (c.next + i + 1) % kSlots;
+                }
+            }
+            if (s) break;
+            g_cv.wait(lock);   // every slot is being filled by another thread
+        }
+        s->held = true;
     }
-    if (s.cap < bytes) {
-        size_t cap = 1 << 16;
-        while (cap < bytes) cap <<= 1;
-        if (s.host) QES_HIP(hipHostFree(s.host));
-        if (s.dev) QES_HIP(hipFree(s.dev));
-        s.host = s.dev = nullptr;
-        s.cap = 0;
-        QES_HIP(hipHostMalloc(&s.host, cap, hipHostMallocDefault));
-        QES_HIP(hipMalloc(&s.dev, cap));
-        s.cap = cap;
+    if (s->in_flight) {
+        const hipError_t e = hipEventSynchronize(s->ev);
+        if (e != hipSuccess) {
+            std::lock_guard<std::mutex> lock(g_mu);
+            s->held = false;
+            g_cv.notify_one();
+            return hip_fail(e);
+        }
+        s->in_flight = false;
     }
-    *out = &s;
+    *out = s;
     return QES_OK;
+}
+
+// Hands the slot back. `enqueued`: device work that reads the slot was put on `stream`; the slot
+// then stays busy until an event recorded now has completed. Returns the event record's status.
+hipError_t release_slot(Slot *s, bool enqueued, hipStream_t stream)
+{
+    hipError_t e = hipSuccess;
+    bool in_flight = false;
+    if (enqueued) {
+        e = hipEventRecord(s->ev, stream);
+        if (e == hipSuccess) in_flight = true;
+        else (void)hipStreamSynchronize(stream);   // no event to wait for later: drain the consumers now
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    s->in_flight = in_flight;
+    s->held = false;
+    g_cv.notify_one();
+    return e;
 }
 
 int tensor_check(const qes_tensor *w)
@@ -131,29 +188,29 @@ int fill_entries(qes::Entry *dst, const uint64_t *seeds_t, const float *fit_t, c
     return QES_OK;
 }
 
-int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
-                  const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
-                  uint64_t *stats, float *residual, int rmode, bool antithetic, void *stream, uint64_t round_seed = 0)
+// Argument checks shared by every single-tensor update / replay entry point.
+int update_check(const qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
+                 const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
+                 const uint64_t *stats, const float *residual, int rmode, bool antithetic)
 {
-    int rc = tensor_check(w);
+    const int rc = tensor_check(w);
     if (rc != QES_OK) return rc;
     if (N <= 0 || N > QES_MAX_POPULATION || hist_len < 0 || hist_len > QES_MAX_HISTORY) return QES_ERR_INVALID_ARG;
     if (antithetic && (N & 1)) return QES_ERR_INVALID_ARG;
-    const bool replay_only = (rmode == 1);
     if (rmode >= 2 && hist_len != 0) return QES_ERR_INVALID_ARG;
     if (hist_len > 0 && (!hist_seeds || !hist_fit)) return QES_ERR_INVALID_ARG;
-    if (!replay_only && (!seeds_t || !fit_t)) return QES_ERR_INVALID_ARG;
+    if (rmode != 1 && (!seeds_t || !fit_t)) return QES_ERR_INVALID_ARG;
     if (rmode != 0 && rmode != 4 && (!residual || ((uintptr_t)residual & 15u) != 0)) return QES_ERR_INVALID_ARG;
     if (!(sigma > 0.0f) || !std::isfinite(sigma) || !std::isfinite(alpha)) return QES_ERR_INVALID_ARG;
     if (!(gamma >= 0.0f && gamma <= 1.0f)) return QES_ERR_INVALID_ARG;
     if (stats && ((uintptr_t)stats & 7u) != 0) return QES_ERR_INVALID_ARG;
+    return QES_OK;
+}
 
-    const double c64 = (double)alpha / ((double)N * (double)sigma);
-    const int32_t steps = hist_len + (replay_only ? 0 : 1);
-    const int32_t records = antithetic ? N / 2 : N;   // one record per member, or per antithetic pair
-    const size_t n_entries = (size_t)steps * (size_t)records;
-    hipStream_t s = (hipStream_t)stream;
-
+// Kernel arguments of a single-tensor update / replay launch (entries are filled in by the caller).
+qes::UpdateArgs update_args(const qes_tensor *w, int32_t steps, int32_t records, float sigma, double c64, float gamma,
+                            uint64_t *stats, float *residual, uint64_t round_seed)
+{
     qes::UpdateArgs a{};
     a.qweight = w->qweight;
     a.entries = nullptr;
@@ -170,24 +227,46 @@ int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit
     a.tensor_id = w->tensor_id;
     a.round_k0 = (uint32_t)round_seed;
     a.round_k1 = (uint32_t)(round_seed >> 32);
+    return a;
+}
 
-    std::lock_guard<std::mutex> lock(g_mu);
+int update_common(const qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
+                  const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
+                  uint64_t *stats, float *residual, int rmode, bool antithetic, void *stream, uint64_t round_seed = 0)
+{
+    int rc = update_check(w, seeds_t, fit_t, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, stats, residual, rmode,
+                          antithetic);
+    if (rc != QES_OK) return rc;
+    const bool replay_only = (rmode == 1);
+    const double c64 = (double)alpha / ((double)N * (double)sigma);
+    const int32_t steps = hist_len + (replay_only ? 0 : 1);
+    const int32_t records = antithetic ? N / 2 : N;   // one record per member, or per antithetic pair
+    const size_t n_entries = (size_t)steps * (size_t)records;
+    hipStream_t s = (hipStream_t)stream;
+    qes::UpdateArgs a = update_args(w, steps, records, sigma, c64, gamma, stats, residual, round_seed);
+
     Slot *slot = nullptr;
     if (n_entries > 0) {
         rc = acquire_slot(n_entries * sizeof(qes::Entry), &slot);
         if (rc != QES_OK) return rc;
         rc = fill_entries((qes::Entry *)slot->host, replay_only ? nullptr : seeds_t, fit_t, hist_seeds, hist_fit,
                           hist_len, N, antithetic, c64);
-        if (rc != QES_OK) return rc;
-        QES_HIP(hipMemcpyAsync(slot->dev, slot->host, n_entries * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
+        if (rc != QES_OK) {
+            (void)release_slot(slot, false, s);
+            return rc;
+        }
+        hipError_t ec = hipMemcpyAsync(slot->dev, slot->host, n_entries * sizeof(qes::Entry), hipMemcpyHostToDevice, s);
+        if (ec != hipSuccess) {
+            (void)release_slot(slot, true, s);
+            return hip_fail(ec);
+        }
         a.entries = (const qes::Entry *)slot->dev;
     }
     hipError_t e = qes::launch_update(a, w->bits, rmode, antithetic, s);
     if (slot) {
         // the slot is busy until everything enqueued so far (copy and kernel) has run
-        hipError_t e2 = hipEventRecord(slot->ev, s);
-        if (e2 == hipSuccess) slot->in_flight = true;
-        else if (e == hipSuccess) e = e2;
+        const hipError_t e2 = release_slot(slot, true, s);
+        if (e == hipSuccess) e = e2;
     }
     if (e != hipSuccess) return hip_fail(e);
     return QES_OK;
@@ -219,31 +298,39 @@ int update_batch_common(const qes_tensor *tensors, int32_t n_tensors, const uint
     const size_t desc_bytes = (size_t)n_tensors * sizeof(qes::TensorDesc);
     hipStream_t s = (hipStream_t)stream;
 
-    std::lock_guard<std::mutex> lock(g_mu);
+    // descriptors grouped by weight width: [all INT4 tensors][all INT8 tensors], blocks numbered per group
+    uint64_t blocks[2] = {0, 0};
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        const uint64_t n_pairs = ((uint64_t)tensors[i].out_features * (uint64_t)tensors[i].in_features) >> 1;
+        blocks[tensors[i].bits == 4 ? 0 : 1] += (n_pairs + 255u) / 256u;
+    }
+    if (blocks[0] >= (1ull << 31) || blocks[1] >= (1ull << 31)) return QES_ERR_UNSUPPORTED;
+
     Slot *slot = nullptr;
     int rc = acquire_slot(entry_bytes + desc_bytes, &slot);
     if (rc != QES_OK) return rc;
     rc = fill_entries((qes::Entry *)slot->host, seeds_t, fit_t, hist_seeds, hist_fit, hist_len, N, antithetic, c64);
-    if (rc != QES_OK) return rc;
-    // descriptors grouped by weight width: [all INT4 tensors][all INT8 tensors], blocks numbered per group
+    if (rc != QES_OK) {
+        (void)release_slot(slot, false, s);
+        return rc;
+    }
     qes::TensorDesc *descs = (qes::TensorDesc *)((char *)slot->host + entry_bytes);
     int32_t count[2] = {0, 0};
-    uint64_t blocks[2] = {0, 0};
     int32_t at = 0;
     for (int g = 0; g < 2; ++g) {
         const int bits = g == 0 ? 4 : 8;
+        uint64_t first_block = 0;
         for (int32_t i = 0; i < n_tensors; ++i) {
             const qes_tensor &w = tensors[i];
             if (w.bits != bits) continue;
             const uint64_t n_pairs = ((uint64_t)w.out_features * (uint64_t)w.in_features) >> 1;
-            descs[at++] = qes::TensorDesc{w.qweight, (uint32_t)n_pairs, (uint32_t)blocks[g], w.qmin,
+            descs[at++] = qes::TensorDesc{w.qweight, (uint32_t)n_pairs, (uint32_t)first_block, w.qmin,
                                           (uint32_t)(w.qmax - w.qmin), w.tensor_id, 0u};
-            blocks[g] += (n_pairs + 255u) / 256u;
+            first_block += (n_pairs + 255u) / 256u;
             ++count[g];
         }
-        if (blocks[g] >= (1ull << 31)) return QES_ERR_UNSUPPORTED;
     }
-    QES_HIP(hipMemcpyAsync(slot->dev, slot->host, entry_bytes + desc_bytes, hipMemcpyHostToDevice, s));
+    hipError_t e = hipMemcpyAsync(slot->dev, slot->host, entry_bytes + desc_bytes, hipMemcpyHostToDevice, s);
 
     qes::UpdateArgs a{};
     a.entries = (const qes::Entry *)slot->dev;
@@ -253,7 +340,6 @@ int update_batch_common(const qes_tensor *tensors, int32_t n_tensors, const uint
     a.sigma = sigma;
     a.c = (float)c64;
     a.gamma = gamma;
-    hipError_t e = hipSuccess;
     const qes::TensorDesc *dev_descs = (const qes::TensorDesc *)((const char *)slot->dev + entry_bytes);
     for (int g = 0; g < 2 && e == hipSuccess; ++g) {
         if (count[g] == 0) continue;
@@ -261,9 +347,8 @@ int update_batch_common(const qes_tensor *tensors, int32_t n_tensors, const uint
         a.n_tensors = count[g];
         e = qes::launch_update_batch(a, g == 0 ? 4 : 8, antithetic, (uint32_t)blocks[g], s);
     }
-    hipError_t e2 = hipEventRecord(slot->ev, s);
-    if (e2 == hipSuccess) slot->in_flight = true;
-    else if (e == hipSuccess) e = e2;
+    const hipError_t e2 = release_slot(slot, true, s);
+    if (e == hipSuccess) e = e2;
     if (e != hipSuccess) return hip_fail(e);
     return QES_OK;
 }
@@ -410,18 +495,18 @@ static int gemm_common(const qes_tensor *w, const uint64_t *seeds, const uint8_t
     if (rc != QES_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
 
+    int8_t *xq = nullptr;
+    float *xs = nullptr;
     if (act_mode == 1) {
         const size_t need = qes_gemm_workspace_bytes(w, N, T, act_mode);
         if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15u) != 0) return QES_ERR_WORKSPACE;
         const size_t rows = (size_t)N * (size_t)T;
-        int8_t *xq = (int8_t *)workspace;
-        float *xs = (float *)((char *)workspace + ((rows * (size_t)w->in_features + 15u) & ~(size_t)15u));
-        QES_HIP(qes::launch_quantize_activations(x, xq, xs, (int64_t)rows, w->in_features, s));
+        xq = (int8_t *)workspace;
+        xs = (float *)((char *)workspace + ((rows * (size_t)w->in_features + 15u) & ~(size_t)15u));
         a.x = xq;
         a.x_scale = xs;
     }
 
-    std::lock_guard<std::mutex> lock(g_mu);
     Slot *slot = nullptr;
     rc = acquire_slot((size_t)N * sizeof(qes::Entry), &slot);
     if (rc != QES_OK) return rc;
@@ -429,12 +514,15 @@ static int gemm_common(const qes_tensor *w, const uint64_t *seeds, const uint8_t
     // and two workgroups still share a CU; longer token counts regenerate the draw per member
     const bool paired = antithetic && qes::gemm_pairs_supported(T, false);
     const int32_t records = fill_gemm_entries((qes::Entry *)slot->host, seeds, perturb_mask, N, antithetic, paired);
-    QES_HIP(hipMemcpyAsync(slot->dev, slot->host, (size_t)records * sizeof(qes::Entry), hipMemcpyHostToDevice, s));
+    // every check that can refuse the call lies above: from here on device work is enqueued
+    hipError_t e = hipSuccess;
+    if (act_mode == 1) e = qes::launch_quantize_activations(x, xq, xs, (int64_t)N * (int64_t)T, w->in_features, s);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(slot->dev, slot->host, (size_t)records * sizeof(qes::Entry), hipMemcpyHostToDevice, s);
     a.entries = (const qes::Entry *)slot->dev;
-    hipError_t e = qes::launch_gemm(a, w->bits, act_mode, paired, s);
-    hipError_t e2 = hipEventRecord(slot->ev, s);
-    if (e2 == hipSuccess) slot->in_flight = true;
-    else if (e == hipSuccess) e = e2;
+    if (e == hipSuccess) e = qes::launch_gemm(a, w->bits, act_mode, paired, s);
+    const hipError_t e2 = release_slot(slot, true, s);
+    if (e == hipSuccess) e = e2;
     if (e != hipSuccess) return hip_fail(e);
     return QES_OK;
 }
@@ -483,8 +571,14 @@ static int gemm_batch_common(const qes_tensor *tensors, int32_t n_tensors, const
     hipStream_t s = (hipStream_t)stream;
     const size_t rows = (size_t)N * (size_t)T;
 
+    // W8A8: every distinct activation tensor gets one region of the workspace and is quantised once
+    struct Quantise {
+        const void *x;
+        char *region;
+        int32_t in_features;
+    };
+    std::vector<Quantise> quantise;
     if (act_mode == 1) {
-        // every distinct activation tensor is quantised once
         const size_t need = qes_gemm_batch_workspace_bytes(tensors, n_tensors, x, N, T, act_mode);
         if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15u) != 0) return QES_ERR_WORKSPACE;
         std::vector<int32_t> which((size_t)n_tensors);
@@ -497,8 +591,7 @@ static int gemm_batch_common(const qes_tensor *tensors, int32_t n_tensors, const
             if (!r) {
                 r = at;
                 at += quantised_bytes(rows, in_f);
-                float *xs = (float *)(r + ((rows * (size_t)in_f + 15u) & ~(size_t)15u));
-                QES_HIP(qes::launch_quantize_activations(x[i], (int8_t *)r, xs, (int64_t)rows, in_f, s));
+                quantise.push_back(Quantise{x[i], r, in_f});
             }
             args[(size_t)i].x = r;
             args[(size_t)i].x_scale = (const float *)(r + ((rows * (size_t)in_f + 15u) & ~(size_t)15u));
@@ -510,52 +603,58 @@ static int gemm_batch_common(const qes_tensor *tensors, int32_t n_tensors, const
     const size_t entry_bytes = (size_t)records * sizeof(qes::Entry);
     const size_t desc_bytes = (size_t)n_tensors * sizeof(qes::GemmArgs);
 
-    std::lock_guard<std::mutex> lock(g_mu);
+    // Launch order: grouped by weight width; inside a group the tensors with the longest rows first
+    // (their workgroups run longest, the short ones then fill the end of the launch). Each tensor
+    // takes ceil(W/8) slots in every XCD's queue.
+    std::vector<int32_t> order[2];
+    uint64_t work[2] = {0, 0};
+    for (int g = 0; g < 2; ++g) {
+        const int bits = g == 0 ? 4 : 8;
+        for (int32_t i = 0; i < n_tensors; ++i)
+            if (tensors[i].bits == bits) order[g].push_back(i);
+        std::stable_sort(order[g].begin(), order[g].end(),
+                         [&](int32_t p, int32_t q) { return tensors[p].in_features > tensors[q].in_features; });
+        for (int32_t i : order[g]) work[g] += (qes::gemm_work_items(tensors[i].out_features, N, paired) + 7u) / 8u;
+        if (work[g] >= (1ull << 27)) return QES_ERR_UNSUPPORTED;
+    }
+
     Slot *slot = nullptr;
     int rc = acquire_slot(entry_bytes + desc_bytes, &slot);
     if (rc != QES_OK) return rc;
     fill_gemm_entries((qes::Entry *)slot->host, seeds, perturb_mask, N, antithetic, paired);
-    // Descriptors grouped by weight width; inside a group the tensors with the longest rows first
-    // (their workgroups run longest, the short ones then fill the end of the launch). Each tensor
-    // takes ceil(W/8) slots in every XCD's queue.
     qes::GemmArgs *descs = (qes::GemmArgs *)((char *)slot->host + entry_bytes);
-    int32_t count[2] = {0, 0};
-    uint64_t work[2] = {0, 0};
     int32_t at = 0;
-    std::vector<int32_t> order;
     for (int g = 0; g < 2; ++g) {
-        const int bits = g == 0 ? 4 : 8;
-        order.clear();
-        for (int32_t i = 0; i < n_tensors; ++i)
-            if (tensors[i].bits == bits) order.push_back(i);
-        std::stable_sort(order.begin(), order.end(),
-                         [&](int32_t p, int32_t q) { return tensors[p].in_features > tensors[q].in_features; });
-        for (int32_t i : order) {
+        uint64_t begin = 0;
+        for (int32_t i : order[g]) {
             qes::GemmArgs d = args[(size_t)i];
             d.entries = (const qes::Entry *)slot->dev;
-            d.work_begin = (uint32_t)work[g];
-            work[g] += (qes::gemm_work_items(d.out_features, N, paired) + 7u) / 8u;
+            d.work_begin = (uint32_t)begin;
+            begin += (qes::gemm_work_items(d.out_features, N, paired) + 7u) / 8u;
             descs[at++] = d;
-            ++count[g];
         }
-        if (work[g] >= (1ull << 27)) return QES_ERR_UNSUPPORTED;
     }
-    QES_HIP(hipMemcpyAsync(slot->dev, slot->host, entry_bytes + desc_bytes, hipMemcpyHostToDevice, s));
-    const qes::GemmArgs *dev_descs = (const qes::GemmArgs *)((const char *)slot->dev + entry_bytes);
+    // every check that can refuse the call lies above: from here on device work is enqueued
     hipError_t e = hipSuccess;
+    for (size_t q = 0; q < quantise.size() && e == hipSuccess; ++q) {
+        const Quantise &z = quantise[q];
+        float *xs = (float *)(z.region + ((rows * (size_t)z.in_features + 15u) & ~(size_t)15u));
+        e = qes::launch_quantize_activations(z.x, (int8_t *)z.region, xs, (int64_t)rows, z.in_features, s);
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(slot->dev, slot->host, entry_bytes + desc_bytes, hipMemcpyHostToDevice, s);
+    const qes::GemmArgs *dev_descs = (const qes::GemmArgs *)((const char *)slot->dev + entry_bytes);
     for (int g = 0; g < 2 && e == hipSuccess; ++g) {
-        if (count[g] == 0) continue;
+        if (order[g].empty()) continue;
         qes::GemmArgs a{};
         a.N = N;
         a.T = T;
-        a.batch = dev_descs + (g == 0 ? 0 : count[0]);
-        a.n_batch = count[g];
+        a.batch = dev_descs + (g == 0 ? 0 : order[0].size());
+        a.n_batch = (int32_t)order[g].size();
         a.work_begin = (uint32_t)work[g];   // slots per XCD queue of this launch
         e = qes::launch_gemm(a, g == 0 ? 4 : 8, act_mode, paired, s);
     }
-    hipError_t e2 = hipEventRecord(slot->ev, s);
-    if (e2 == hipSuccess) slot->in_flight = true;
-    else if (e == hipSuccess) e = e2;
+    const hipError_t e2 = release_slot(slot, true, s);
+    if (e == hipSuccess) e = e2;
     if (e != hipSuccess) return hip_fail(e);
     return QES_OK;
 }
@@ -664,16 +763,17 @@ int qes_update_stochastic_rounding(qes_tensor *w, const uint64_t *seeds_t, const
 int qes_normalize_fitness(const float *reward, int32_t N, float *fit)
 {
     if (!reward || !fit || N <= 0) return QES_ERR_INVALID_ARG;
-    double mu = 0.0;
-    for (int32_t i = 0; i < N; ++i) mu += (double)reward[i];
-    mu /= (double)N;
-    double var = 0.0;
+    // running mean and sum of squared deviations, updated member by member (Welford), in fp64
+    double mean = 0.0, m2 = 0.0;
     for (int32_t i = 0; i < N; ++i) {
-        const double d = (double)reward[i] - mu;
-        var += d * d;
+        const double r = (double)reward[i];
+        const double before = r - mean;
+        mean += before / (double)(i + 1);
+        m2 += before * (r - mean);
     }
-    const double sd = std::sqrt(var / (double)N);
-    for (int32_t i = 0; i < N; ++i) fit[i] = (N < 2 || sd == 0.0) ? 0.0f : (float)(((double)reward[i] - mu) / sd);
+    const double spread = std::sqrt(m2 / (double)N);   // population standard deviation
+    const bool flat = N < 2 || !(spread > 0.0);
+    for (int32_t i = 0; i < N; ++i) fit[i] = flat ? 0.0f : (float)(((double)reward[i] - mean) / spread);
     return QES_OK;
 }
 
@@ -682,6 +782,13 @@ int qes_bench_noise(int32_t mode, uint64_t n_threads, int32_t iters, float sigma
     if ((mode != 0 && mode != 1) || !sink || n_threads == 0 || n_threads > (1ull << 31) || iters < 0)
         return QES_ERR_INVALID_ARG;
     QES_HIP(qes::launch_bench_noise(mode, n_threads, iters, sigma, sink, (hipStream_t)stream));
+    return QES_OK;
+}
+
+int qes_bench_mfma(int32_t mode, uint32_t n_blocks, int32_t iters, uint32_t *sink, void *stream)
+{
+    if ((mode != 0 && mode != 1) || !sink || n_blocks == 0 || n_blocks > (1u << 20) || iters < 0) return QES_ERR_INVALID_ARG;
+    QES_HIP(qes::launch_bench_mfma(mode, n_blocks, iters, sink, (hipStream_t)stream));
     return QES_OK;
 }
 

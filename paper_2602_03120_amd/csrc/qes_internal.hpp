@@ -72,6 +72,7 @@ hipError_t launch_noise_from_words(const uint32_t *words4, uint64_t n, float sig
                                    hipStream_t s);
 hipError_t launch_bench_noise(int mode, uint64_t n_threads, int iters, float sigma, uint32_t *sink,
                               hipStream_t s);
+hipError_t launch_bench_mfma(int mode, uint32_t n_blocks, int iters, uint32_t *sink, hipStream_t s);
 hipError_t launch_bench_copy(const void *src, void *dst, size_t n_bytes, hipStream_t s);
 
 // bits: 4|8; rmode 0: Alg. 2 in place; 1: replay only, residual written; 2: Alg. 1 step on a stored residual

@@ -1,6 +1,7 @@
-// Noise probes (bit-for-bit test access to the generator of docs/NOISE_SPEC.md) and the two
-// ceiling microbenchmarks the benchmark reports next to the kernels: noise draws per second with
-// no memory traffic, and a plain streaming copy.
+// Noise probes (bit-for-bit test access to the generator of docs/NOISE_SPEC.md) and the ceiling
+// microbenchmarks the benchmark reports next to the kernels: Philox words and noise draws per
+// second with no memory traffic, matrix instructions per second on register operands, and a plain
+// streaming copy.
 #include "qes_internal.hpp"
 #include "qes_noise.hpp"
 
@@ -58,28 +59,86 @@ __global__ __launch_bounds__(kBlock) void noise_from_words_kernel(const uint4 *_
     if (delta2) delta2[j] = make_char2((signed char)delta_of(g0, w.z, sigma), (signed char)delta_of(g1, w.w, sigma));
 }
 
+// Noise ceiling: what the generator alone sustains, in the shape the tensor kernels run it in: four
+// independent chains per thread (four members of one pair at a time, each with its own
+// wave-uniform key), eight waves per SIMD, no memory traffic in the loop. MODE 0: Philox words only;
+// MODE 1: full pair draws (Philox + Box-Muller + two stochastic roundings, δ kept in fp32).
+constexpr int kChains = 4;
+
 template <int MODE>
-__global__ __launch_bounds__(kBlock) void bench_noise_kernel(uint64_t n_threads, int iters, float sigma,
-                                                             uint32_t *__restrict__ sink)
+__global__ __launch_bounds__(kBlock, 8) void bench_noise_kernel(uint64_t n_threads, int iters, float sigma,
+                                                                uint32_t *__restrict__ sink)
 {
     const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     if (t >= n_threads) return;
     uint32_t acc = 0;
+    float facc = 0.0f;
     const uint32_t pair = (uint32_t)t;
-    // the key changes per iteration and is wave-uniform, as in the real kernels (one member per step)
-    for (int it = 0; it < iters; ++it) {
-        const uint32_t k0 = 0x1234567u + (uint32_t)it * 0x9E3779B1u;
-        const uint32_t k1 = 0x89ABCDEu ^ (uint32_t)it;
+    for (int it = 0; it < iters; it += kChains) {
+        uint32_t k0[kChains], k1[kChains];
+#pragma unroll
+        for (int m = 0; m < kChains; ++m) {
+            k0[m] = 0x1234567u + (uint32_t)(it + m) * 0x9E3779B1u;   // wave-uniform, as a member's seed is
+            k1[m] = 0x89ABCDEu ^ (uint32_t)(it + m);
+        }
         if (MODE == 0) {
-            const Words w = philox_tensor(pair, 7u, k0, k1);
-            acc ^= w.w0 ^ w.w1 ^ w.w2 ^ w.w3;
+            Words w[kChains];
+#pragma unroll
+            for (int m = 0; m < kChains; ++m) w[m] = philox_tensor(pair, 7u, k0[m], k1[m]);
+#pragma unroll
+            for (int m = 0; m < kChains; ++m) acc ^= w[m].w0 ^ w[m].w1 ^ w[m].w2 ^ w[m].w3;
         } else {
-            int32_t d0, d1;
-            delta_pair(k0, k1, 7u, pair, sigma, d0, d1);
-            acc += (uint32_t)(d0 * 16 + d1);
+            float d0[kChains], d1[kChains];
+#pragma unroll
+            for (int m = 0; m < kChains; ++m) delta_pair_f32<false>(k0[m], k1[m], 7u, pair, sigma, d0[m], d1[m]);
+#pragma unroll
+            for (int m = 0; m < kChains; ++m) facc += d0[m] * 16.0f + d1[m];
         }
     }
-    sink[t] = acc;
+    sink[t] = acc + (uint32_t)(int32_t)facc;
+}
+
+// MFMA ceiling: eight independent accumulator tiles per wave, operands in registers, no memory.
+// MODE 0: v_mfma_f32_16x16x32_bf16 (16384 flop per wave instruction); MODE 1: v_mfma_i32_16x16x64_i8
+// (32768 op). Two waves per SIMD.
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
+typedef __attribute__((ext_vector_type(4))) float probe_f32x4;
+typedef __attribute__((ext_vector_type(4))) int probe_i32x4;
+constexpr int kMfmaTiles = 8;
+
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void bench_mfma_kernel(int iters, uint32_t *__restrict__ sink)
+{
+    union {
+        uint32_t u[4];
+        probe_bf16x8 bf;
+        probe_i32x4 i8;
+    } a, b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a.u[i] = 0x3F803F80u ^ (threadIdx.x & 0x7Fu);   // finite bf16 pairs near 1 / arbitrary int8 quadruples
+        b.u[i] = 0x3F003F00u ^ (uint32_t)i;
+    }
+    probe_f32x4 cf[kMfmaTiles];
+    probe_i32x4 ci[kMfmaTiles];
+#pragma unroll
+    for (int t = 0; t < kMfmaTiles; ++t) {
+        cf[t] = probe_f32x4{0, 0, 0, 0};
+        ci[t] = probe_i32x4{0, 0, 0, 0};
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < kMfmaTiles; ++t) {
+            if (MODE == 0) cf[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.bf, b.bf, cf[t], 0, 0, 0);
+            else ci[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a.i8, b.i8, ci[t], 0, 0, 0);
+        }
+    }
+    uint32_t acc = 0;
+#pragma unroll
+    for (int t = 0; t < kMfmaTiles; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc ^= (MODE == 0) ? __float_as_uint(cf[t][j]) : (uint32_t)ci[t][j];
+    sink[(size_t)blockIdx.x * kBlock + threadIdx.x] = acc;
 }
 
 __global__ __launch_bounds__(kBlock) void copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
@@ -135,6 +194,14 @@ hipError_t launch_bench_noise(int mode, uint64_t n_threads, int iters, float sig
         bench_noise_kernel<0><<<blocks_for(n_threads), kBlock, 0, s>>>(n_threads, iters, sigma, sink);
     else
         bench_noise_kernel<1><<<blocks_for(n_threads), kBlock, 0, s>>>(n_threads, iters, sigma, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_bench_mfma(int mode, uint32_t n_blocks, int iters, uint32_t *sink, hipStream_t s)
+{
+    if (n_blocks == 0) return hipSuccess;
+    if (mode == 0) bench_mfma_kernel<0><<<n_blocks, kBlock, 0, s>>>(iters, sink);
+    else bench_mfma_kernel<1><<<n_blocks, kBlock, 0, s>>>(iters, sink);
     return hipGetLastError();
 }
 

@@ -127,9 +127,15 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs args
         a.tensor_id = td.tensor_id;
         block -= td.first_block;
     }
-    const uint32_t t = block * kBlock + threadIdx.x;
+    // A wave that lies wholly past the tensor leaves. In the wave that straddles the end, the lanes
+    // past it stay alive for the wavefront reduction of the counters: they redo the last thread's
+    // work (in bounds), store nothing and count nothing. n_pairs is a multiple of PPT (host-checked).
+    const uint32_t wave_first = (block * kBlock + (threadIdx.x & ~63u)) * PPT;
+    if (wave_first >= a.n_pairs) return;
+    uint32_t t = block * kBlock + threadIdx.x;
+    const bool active = t * PPT < a.n_pairs;
+    if (!active) t = a.n_pairs / PPT - 1u;
     const uint32_t pair0 = t * PPT;
-    if (pair0 >= a.n_pairs) return;   // n_pairs is a multiple of PPT (checked on the host)
 
     Raw<kBytes> raw;
     raw.load(a.qweight, (size_t)t * kBytes);
@@ -213,7 +219,14 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs args
                 d = (int32_t)fl + ((ub < u - fl) ? 1 : 0);
             } else {
                 u = __builtin_fmaf(a.c, g[j], a.gamma * res[j]);
-                d = (int32_t)__builtin_rintf(u);
+                float r = __builtin_rintf(u);
+                if (RMODE == 2 || RMODE == 3) {
+                    // the stored residual is caller data: saturate like the conversion is defined to
+                    // (NaN -> 0); elsewhere the host has bounded |u| below 2^30
+                    r = __builtin_fminf(__builtin_fmaxf(r, -2147483648.0f), 2147483520.0f);
+                    r = (u != u) ? 0.0f : r;
+                }
+                d = (int32_t)r;
             }
             const int32_t nv = gate(wq[j], d, a.qmin, a.qspan);
             const int32_t df = nv - wq[j];
@@ -226,18 +239,22 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs args
         }
     }
 
-    if (RMODE == 1 || RMODE == 2) {
+    if (!active) {
+        changed = 0;
+        gated = 0;
+    }
+    if (active && (RMODE == 1 || RMODE == 2)) {
         float *out = a.residual + (size_t)pair0 * 2;
 #pragma unroll
         for (int j = 0; j < 2 * PPT; ++j) out[j] = res[j];
     }
-    if (RMODE == 3) {
+    if (active && RMODE == 3) {
         _Float16 *out = (_Float16 *)a.residual + (size_t)pair0 * 2;
 #pragma unroll
         for (int j = 0; j < 2 * PPT; ++j) out[j] = (_Float16)fminf(fmaxf(res[j], -65504.0f), 65504.0f);
     }
     if (RMODE != 1) {
-        if (changed) {
+        if (changed) {   // zero in the lanes past the end
 #pragma unroll
             for (int j = 0; j < PPT; ++j) raw.set_pair_bits(j, P::kBytesPerPair, P::pack(wq[2 * j], wq[2 * j + 1]));
             raw.store(a.qweight, (size_t)t * kBytes);

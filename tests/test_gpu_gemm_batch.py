@@ -100,3 +100,31 @@ def test_batch_argument_errors(env):
         qes.perturbed_qgemm_batch(dts, seeds, 1.0, xs, ys, act_mode=1)
     with pytest.raises(ValueError):                      # an output of the wrong shape
         qes.perturbed_qgemm_batch(dts, seeds, 1.0, xs, [ys[0], ys[0]])
+
+
+def test_refused_w8a8_call_leaves_the_workspace_untouched(env):
+    """Every check that can refuse a call precedes the first launch: a W8A8 batch that passes the
+    per-tensor checks but exceeds the launch's work-queue limit (4096 descriptors of one 16384-row
+    tensor, 1024 members: 2^27 queue slots) returns QES_ERR_UNSUPPORTED before its activations are
+    quantised into the workspace. All descriptors alias the same valid buffers."""
+    torch, qes, u = env["torch"], env["qes"], env["u"]
+    out_f, in_f, N, T = 16384, 32, 1024, 1
+    qw = torch.zeros((out_f, in_f), dtype=torch.int8, device=u.DEV)
+    sc = torch.ones(out_f, dtype=torch.float16, device=u.DEV)
+    t = qes.Tensor(qw, sc, out_f, in_f, 8, 0, -127, 127, 5)
+    x = torch.ones((N, T, in_f), dtype=torch.bfloat16, device=u.DEV)
+    y = torch.zeros((N, T, out_f), dtype=torch.bfloat16, device=u.DEV)
+    n = 4096
+    nbytes = qes.gemm_batch_workspace_bytes([t] * n, [x] * n, N, T, 1)
+    assert nbytes > 0
+    ws = torch.full((nbytes,), 0xAB, dtype=torch.uint8, device=u.DEV)
+    with pytest.raises(qes.QesError) as err:
+        qes.perturbed_qgemm_batch([t] * n, np.arange(N, dtype=np.uint64), 1.0, [x] * n, [y] * n, act_mode=1, workspace=ws)
+    assert err.value.status == -2
+    torch.cuda.synchronize()
+    assert bool((ws == 0xAB).all()) and bool((y == 0).all())
+    # the single-tensor call on the same buffers is accepted and does write the workspace
+    small = qes.gemm_workspace_bytes(t, N, T, 1)
+    qes.perturbed_qgemm(t, np.arange(N, dtype=np.uint64), 1.0, x, y, act_mode=1, workspace=ws[:small])
+    torch.cuda.synchronize()
+    assert not bool((ws[:small] == 0xAB).all())
