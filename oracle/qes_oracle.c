@@ -542,7 +542,8 @@ int oracle_replay_residual(const oracle_tensor *w, const uint64_t *hist_seeds, c
 /*
  * Alg. 2 in full: replay the history, then apply the new population's step to the weights in
  * place. stats (may be NULL): stats[0] += number of elements whose weight changed, stats[1] +=
- * number of elements whose non-zero rounded update was masked by the gate (final step only).
+ * number of elements whose non-zero rounded update was masked by the gate (final step only; Eq. 4
+ * masks updates, so a zero update is never counted, whatever the stored weight is).
  */
 int oracle_update(oracle_tensor *w, const uint64_t *seeds_t, const float *fit_t,
                   const uint64_t *hist_seeds, const float *hist_fit, int32_t hist_len, int32_t N,
@@ -649,11 +650,11 @@ int oracle_update_stochastic_rounding(oracle_tensor *w, const uint64_t *seeds_t,
                 const float fr = u - fl;
                 const int32_t d = sat_i32(fl) + ((ub < fr) ? 1 : 0);
                 const int64_t v = (int64_t)wq + (int64_t)d;
-                if (v >= w->qmin && v <= w->qmax) {
-                    if (d != 0) { store_q(w, n, k + l, (int32_t)v); ++changed; }
-                } else {
-                    ++gated;
-                }
+                /* Eq. 4 masks a perturbation that would leave the range; a zero update has nothing
+                 * to mask, also when the stored weight itself lies outside [qmin, qmax] */
+                if (d == 0) continue;
+                if (v >= w->qmin && v <= w->qmax) { store_q(w, n, k + l, (int32_t)v); ++changed; }
+                else ++gated;
             }
         }
     }

@@ -5,6 +5,7 @@ trajectory at one residual."""
 import numpy as np
 import pytest
 
+import workloads as wl
 from test_oracle_update import _tensor
 
 
@@ -111,3 +112,39 @@ def test_range_edge_is_masked_and_counted(oracle):
     up = g > 0.2                                                   # u >= 1.6: Δ >= 1 whatever the uniform
     assert up.any() and (after[up] == 7).all()
     assert stats[1] >= up.sum() and stats[0] == (after != 7).sum()
+
+
+def test_a_zero_update_is_never_counted_as_gated(oracle):
+    """Eq. 4 masks an update that would leave the range; with nothing to mask nothing is counted,
+    also where the stored weight itself lies outside [qmin, qmax] (a -8 nibble under the symmetric
+    range [-7, 7] of App. A.1). Both update rules use the same counter rule."""
+    out_f, in_f, N = 4, 32, 4
+    q = np.full((out_f, in_f), -8, dtype=np.int64)
+    q[:, ::3] = 2
+    seeds = np.arange(1, N + 1, dtype=np.uint64)
+    mk = lambda: oracle.Tensor(wl.pack_int4(q), None, out_f, in_f, 4, 0, -7, 7, 3)   # noqa: E731
+    # zero fitness: every update is zero -> no change, nothing gated
+    for call in (lambda w: oracle.update_stochastic_rounding(w, seeds, np.zeros(N, np.float32), 1.0, 2.0, 5),
+                 lambda w: oracle.update(w, seeds, np.zeros(N, np.float32), None, None, 1.0, 2.0, 0.9)):
+        w = mk()
+        stats = call(w)
+        assert (stats == 0).all() and (w.unpacked() == q).all()
+    # non-zero fitness: exactly the elements whose rounded update is non-zero and masked are counted
+    fit = np.float32([1.5, -0.5, -1.5, 0.5])
+    w = mk()
+    g = oracle.aggregate(w, seeds, fit, 1.0)
+    u = (np.float32(2.0 / N) * g).astype(np.float32)
+    d = np.rint(u).astype(np.int64)
+    stats = oracle.update(w, seeds, fit, None, None, 1.0, 2.0, 0.9)
+    ok = (q + d >= -7) & (q + d <= 7)
+    assert stats[0] == ((d != 0) & ok).sum() and stats[1] == ((d != 0) & ~ok).sum() and stats[1] > 0
+    assert (w.unpacked() == np.where(ok, q + d, q)).all()
+    # the stochastic rule on the same tensor: Δ is floor or floor + 1; the counter follows the Δ taken
+    w = mk()
+    stats = oracle.update_stochastic_rounding(w, seeds, fit, 1.0, 2.0, 9)
+    step = w.unpacked() - q
+    ub = _uniforms(oracle, 9, 3, out_f * in_f // 2).reshape(out_f, in_f)
+    d = (np.floor(u) + (ub < (u - np.floor(u)))).astype(np.int64)
+    ok = (q + d >= -7) & (q + d <= 7)
+    assert (step == np.where(ok, d, 0)).all()
+    assert stats[0] == ((d != 0) & ok).sum() and stats[1] == ((d != 0) & ~ok).sum() and stats[1] > 0
