@@ -22,5 +22,21 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+def build_driver(out_dir: str, sanitized: bool) -> str:
+    """The oracle and oracle/sanitize_driver.c in one program. sanitized: AddressSanitizer and
+    UndefinedBehaviorSanitizer, runtimes linked statically, every report fatal; otherwise the
+    oracle's ordinary flags. Returns the program's path."""
+    exe = os.path.join(out_dir, "oracle_driver_sanitized" if sanitized else "oracle_driver_plain")
+    if sanitized:
+        flags = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                 "-static-libasan", "-static-libubsan"]
+    else:
+        flags = ["-O2"]
+    cmd = ["gcc"] + flags + ["-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-Wall", "-Wextra", "-o", exe, SRC,
+                             os.path.join(HERE, "sanitize_driver.c"), "-lm"]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 if __name__ == "__main__":
     print(build(force="--if-stale" not in sys.argv))

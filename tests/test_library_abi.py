@@ -33,6 +33,23 @@ def test_host_only_entry_points():
     assert (qes.normalize_fitness(np.full(7, 2.0, dtype=np.float32)) == 0).all()
 
 
+def test_normalize_fitness_against_numpy():
+    """The library's own normalisation (a one-pass running mean / squared-deviation update) against
+    numpy's fp64 z-score with the population standard deviation."""
+    import paper_2602_03120_amd as qes
+    rng = np.random.default_rng(11)
+    for N in (2, 3, 8, 30, 64, 1000, 1024):
+        for shift, scale in ((0.0, 1.0), (100.0, 1.0), (-3.0, 1e-3), (1e4, 50.0)):
+            r = (rng.standard_normal(N) * scale + shift).astype(np.float32)
+            r64 = r.astype(np.float64)
+            ref = ((r64 - r64.mean()) / r64.std()).astype(np.float32)
+            got = qes.normalize_fitness(r)
+            assert (np.abs(got - ref) <= 2 * np.spacing(np.abs(ref)) + 1e-12).all(), (N, shift, scale)
+            assert abs(got.astype(np.float64).mean()) < 1e-6 and abs(got.astype(np.float64).std() - 1) < 1e-6
+    assert (qes.normalize_fitness(np.float32([5.0])) == 0).all()                # N < 2
+    assert (qes.normalize_fitness(np.float32([1e-20, 1e-20, 1e-20])) == 0).all()
+
+
 def test_product_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2602_03120_amd")
     for dirpath, _, files in os.walk(pkg):

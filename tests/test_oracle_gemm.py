@@ -143,3 +143,34 @@ def test_int4_nibble_order(oracle):
     x = wl.f32_to_bf16_bits(np.eye(in_f, dtype=np.float32)[None])   # N=1, T=in_f
     y = wl.bf16_bits_to_f32(oracle.perturbed_qgemm(w, [1], 0.0, x))[0]
     assert (y.T == q).all()
+
+
+def test_output_rounding_is_nearest_even_bfloat16(oracle):
+    """The final rounding to bfloat16 on exact ties and next to them, against hand-placed values:
+    with unit weights and scale 1 the output is x0 + x1 exactly, and x1 = 2^-8 puts it half-way
+    between two bfloat16 neighbours of x0 in [1, 2). Truncation, round-half-up and round-half-away
+    each miss at least one of the cases."""
+    one = wl.pack_int4(np.ones((1, 2), dtype=np.int64))
+    scale = wl.f16_bits(np.ones((1, 1), dtype=np.float32))
+    w = oracle.Tensor(one, scale, 1, 2, 4, 2, -8, 7, 1)
+    cases = [
+        (0x3F80, 0x3B80, 0x3F80),   # 1 + 2^-8: tie, lower neighbour 1.0 is even
+        (0x3F81, 0x3B80, 0x3F82),   # 1 + 2^-7 + 2^-8: tie, upper neighbour is even
+        (0xBF80, 0xBB80, 0xBF80),   # the same two, negated
+        (0xBF81, 0xBB80, 0xBF82),
+        (0x3F80, 0x3B81, 0x3F81),   # just above the tie: up
+        (0x3F81, 0x3B7F, 0x3F81),   # just below the tie: down
+        (0x3F80, 0x3A80, 0x3F80),   # a quarter of a step: down
+        (0x3F80, 0x3BC0, 0x3F81),   # three quarters of a step: up
+    ]
+    x = np.array([[[a, b]] for a, b, _ in cases], dtype=np.uint16)            # [N=8, T=1, in=2]
+    y = oracle.perturbed_qgemm(w, np.zeros(len(cases), dtype=np.uint64), 0.0, x)
+    assert [int(v) for v in y.reshape(-1)] == [c for _, _, c in cases]
+    # the exact values behind the table, restated in rationals
+    from fractions import Fraction
+    def val(bits):
+        return Fraction(float(wl.bf16_bits_to_f32(np.array([bits], dtype=np.uint16))[0]))
+    for a, b, c in cases:
+        exact = val(a) + val(b)
+        lo_hi = sorted([val(c), val(c ^ 1)], key=lambda v: abs(v - exact))
+        assert abs(val(c) - exact) <= abs(lo_hi[1] - exact)

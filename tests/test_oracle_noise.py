@@ -28,6 +28,39 @@ def test_philox_known_answers(oracle):
     assert n == 3
 
 
+def _philox_forward(ctr, key):
+    """Philox4x32-10 in plain Python integers, written from the published round (N1): a third
+    implementation next to the C oracle and the HIP kernels."""
+    c0, c1, c2, c3 = (int(v) for v in ctr)
+    k0, k1 = (int(v) for v in key)
+    for rnd in range(10):
+        if rnd:
+            k0, k1 = (k0 + W0) & MASK, (k1 + W1) & MASK
+        p0, p1 = M0 * c0, M1 * c2
+        c0, c1, c2, c3 = (p1 >> 32) ^ c1 ^ k0, p1 & MASK, (p0 >> 32) ^ c3 ^ k1, p0 & MASK
+    return [c0, c1, c2, c3]
+
+
+def test_philox_against_big_integer_python(oracle):
+    for line in open(os.path.join(HERE, "golden", "philox4x32_10_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        v = [int(t, 16) for t in line.split()]
+        assert _philox_forward(v[0:4], v[4:6]) == v[6:10]
+    rng = np.random.default_rng(7)
+    cases = [([0, 0, 0, 0], [0, 1]), ([1, 0, 0, 0], [0, 0]), ([0, 0, 0, 1], [0, 0]), ([MASK, 0, MASK, 0], [MASK, 0])]
+    cases += [([int(x) for x in rng.integers(0, 1 << 32, size=4)], [int(x) for x in rng.integers(0, 1 << 32, size=2)])
+              for _ in range(500)]
+    for ctr, key in cases:
+        assert [int(x) for x in oracle.philox4x32_10(ctr, key)] == _philox_forward(ctr, key)
+    # the tensor stream: counter (pair lo, pair hi, tensor id, 0), key (seed lo, seed hi)
+    seed, tid = 0x0123456789ABCDEF, 77
+    w = oracle.noise_words(seed, tid, (1 << 32) - 3, 6)
+    for j in range(6):
+        pair = (1 << 32) - 3 + j
+        assert [int(x) for x in w[j]] == _philox_forward([pair & MASK, pair >> 32, tid, 0], [seed & MASK, seed >> 32])
+
+
 def _philox_decrypt(out, key):
     """Inverse of the 10-round bijection, from the round's algebra (uses the modular inverses of
     the multipliers, which the forward direction never touches)."""
@@ -205,3 +238,123 @@ def test_radius_is_correctly_rounded_sqrt_for_every_input(oracle):
     r = np.sqrt((np.float32(-2.0) * L).astype(np.float64)).astype(np.float32)
     assert (eps[::97, 0] == r * cp0).all()
     assert (eps[:, 1] == 0).all()                      # sin(0) = 0: the odd lane is r * 0
+
+
+# ---- an independent numpy-float32 implementation of N3-N5 of docs/NOISE_SPEC.md -------------------
+# Written from the definition's text and coefficient tables (hex-float column), vectorised, with the
+# fused multiply-add emulated exactly: the product of two fp32 values is exact in fp64, the fp64
+# addition's rounding error is recovered with the two-sum identity, and a sum that lands exactly on
+# an fp32 rounding boundary while the exact value does not is nudged off it before the final
+# rounding, so that rounding once (fma) and rounding twice (fp64 then fp32) cannot differ.
+
+def _f32(x):
+    return np.asarray(x, dtype=np.float32)
+
+
+def _fma32(a, b, c):
+    a, b, c = (np.asarray(v, dtype=np.float32).astype(np.float64) for v in (a, b, c))
+    p = a * b
+    s = p + c
+    bb = s - p
+    err = (p - (s - bb)) + (c - bb)
+    on_boundary = (s.view(np.uint64) & np.uint64(0x1FFFFFFF)) == np.uint64(0x10000000)
+    toward = np.where(err > 0, np.inf, -np.inf)
+    s = np.where(on_boundary & (err != 0), np.nextafter(s, toward), s)
+    return s.astype(np.float32)
+
+
+_H = float.fromhex
+_LN2 = _f32(_H("0x1.62e430p-1"))
+_LP = [_f32(_H(h)) for h in ("-0x1.000060p-1", "0x1.5559f0p-2", "-0x1.ff7476p-3", "0x1.976dd8p-3", "-0x1.6049d0p-3",
+                             "0x1.4d64acp-3", "-0x1.a7d988p-4")]
+_SP = [_f32(_H(h)) for h in ("0x1.921fb6p+0", "-0x1.4abbc4p-1", "0x1.4668f2p-4", "-0x1.32535ap-8", "0x1.3e17cap-13")]
+_CP = [_f32(_H(h)) for h in ("0x1.fffffep-1", "-0x1.3bd3a6p+0", "0x1.03bd06p-2", "-0x1.54f61ap-6", "0x1.c1f064p-11")]
+
+
+def _numpy_noise(words, sigma):
+    """(eps [n,2] float32, delta [n,2] int64) of n Philox word quadruples, per N3-N6."""
+    w = np.asarray(words, dtype=np.uint32).reshape(-1, 4)
+    m = (w[:, 0] >> np.uint32(8)) + np.uint32(1)
+    q = w[:, 1] >> np.uint32(30)
+    f = ((w[:, 1] >> np.uint32(6)) & np.uint32(0xFFFFFF)).astype(np.float32) * _f32(2.0 ** -24)
+    ub = [(w[:, 2] >> np.uint32(8)).astype(np.float32) * _f32(2.0 ** -24),
+          (w[:, 3] >> np.uint32(8)).astype(np.float32) * _f32(2.0 ** -24)]
+    # ln
+    ix = m.astype(np.float32).view(np.uint32) - np.uint32(0x3F3504F3)
+    e = (ix >> np.uint32(23)).astype(np.int64)
+    t = ((ix & np.uint32(0x007FFFFF)) + np.uint32(0x3F3504F3)).view(np.float32) - _f32(1.0)
+    p = np.full_like(t, _LP[6])
+    for k in (5, 4, 3, 2, 1, 0):
+        p = _fma32(p, t, _LP[k])
+    l1 = _fma32(t * t, p, t)
+    L = _fma32((e - 24).astype(np.float32), _LN2, l1)
+    r = np.sqrt(_f32(-2.0) * L)
+    # sin / cos of the first-quadrant angle
+    z = f * f
+    sp = np.full_like(z, _SP[4])
+    cp = np.full_like(z, _CP[4])
+    for k in (3, 2, 1, 0):
+        sp = _fma32(sp, z, _SP[k])
+        cp = _fma32(cp, z, _CP[k])
+    s = f * sp
+    c1 = np.select([q == 0, q == 1, q == 2], [cp, -s, -cp], s)
+    s1 = np.select([q == 0, q == 1, q == 2], [s, cp, -s], -cp)
+    eps = np.stack([r * c1, r * s1], axis=1).astype(np.float32)
+    delta = np.empty(eps.shape, dtype=np.int64)
+    for lane in range(2):
+        tt = _f32(sigma) * eps[:, lane]
+        fl = np.floor(tt)
+        fr = tt - fl
+        delta[:, lane] = np.clip(fl.astype(np.int64) + (ub[lane] < fr), -8, 7)
+    return eps, delta
+
+
+def test_fma_emulation_is_exact():
+    # against exact rational arithmetic, on operands that provoke double rounding
+    from fractions import Fraction
+    rng = np.random.default_rng(3)
+    a = rng.standard_normal(4000).astype(np.float32)
+    b = rng.standard_normal(4000).astype(np.float32)
+    c = (-(a.astype(np.float64) * b.astype(np.float64))).astype(np.float32)     # heavy cancellation
+    c[::2] = rng.standard_normal(2000).astype(np.float32)
+    # exact ties of the fp32 result grid: 1 + 2^-24 (+ a crumb that must break the tie)
+    a = np.concatenate([a, _f32([1.0, 1.0, 1.0, 3.0])])
+    b = np.concatenate([b, _f32([2.0 ** -24, 2.0 ** -24 + 2.0 ** -47, 2.0 ** -24 - 2.0 ** -48, 2.0 ** -24])])
+    c = np.concatenate([c, _f32([1.0, 1.0, 1.0, 1.0 + 2.0 ** -23])])
+    got = _fma32(a, b, c)
+
+    def round_f32(x):          # nearest-even rounding of a rational to fp32 (normal range)
+        if x == 0:
+            return 0.0
+        sign, x = (-1, -x) if x < 0 else (1, x)
+        e = 0
+        while x >= 2:
+            x, e = x / 2, e + 1
+        while x < 1:
+            x, e = x * 2, e - 1
+        scaled = x * (1 << 23)
+        n = int(scaled)
+        rem = scaled - n
+        if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and n & 1):
+            n += 1
+        return sign * float(Fraction(n, 1 << 23) * Fraction(2) ** e)
+
+    for i in range(a.size):
+        exact = Fraction(float(a[i])) * Fraction(float(b[i])) + Fraction(float(c[i]))
+        assert float(got[i]) == round_f32(exact), i
+
+
+@pytest.mark.parametrize("sigma", [1.0, 0.37, 2.5, 0.01])
+def test_numpy_float32_reimplementation_matches_bit_for_bit(oracle, sigma):
+    seed, tid, n = 0xA5A5A5A55A5A5A5A, 21, 60000
+    w = oracle.noise_words(seed, tid, 12345, n)
+    eps_ref, delta_ref = oracle.noise_from_words(w, sigma)
+    eps, delta = _numpy_noise(w, sigma)
+    assert (eps.view(np.uint32) == eps_ref.view(np.uint32)).all()
+    assert (delta == delta_ref).all()
+    # edge inputs: smallest and largest radius uniform, every quadrant, angle 0 and just below 1
+    edge = np.array([[r, a, 0x80000000, 0x7FFFFF00] for r in (0, 0xFF, 0xFFFFFF00, 0xFFFFFFFF, 0x80000000)
+                     for a in (0, 0x3FFFFFC0, 0x40000000, 0x7FFFFFFF, 0x80000040, 0xC0000000, 0xFFFFFFFF)], dtype=np.uint32)
+    eps_ref, delta_ref = oracle.noise_from_words(edge, sigma)
+    eps, delta = _numpy_noise(edge, sigma)
+    assert (eps.view(np.uint32) == eps_ref.view(np.uint32)).all() and (delta == delta_ref).all()
