@@ -349,7 +349,8 @@ int oracle_perturbed_qgemm(const oracle_tensor *w, const uint64_t *seeds, const 
         xq = (int8_t *)malloc((size_t)N * T * K);
         ascale = (float *)malloc((size_t)N * T * sizeof(float));
         if (!xq || !ascale) { free(xq); free(ascale); return ORACLE_ERR_INVALID_ARG; }
-        for (int64_t it = 0; it < (int64_t)N * T; ++it) {
+#pragma omp parallel for schedule(static)
+        for (int64_t it = 0; it < (int64_t)N * T; ++it) {   /* tokens are independent */
             float amax = 0.0f;
             for (int64_t k = 0; k < K; ++k) {
                 float v = fabsf(u2f((uint32_t)x[it * K + k] << 16));

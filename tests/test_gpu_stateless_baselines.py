@@ -42,6 +42,31 @@ def test_steps_match_oracle(env, bits, out_f, in_f, N, steps, alpha):
     assert ref_stats[0] > 0 and (out_f * in_f < 10000 or ref_stats[1] > 0)
 
 
+def test_stored_weights_outside_the_range_are_not_counted_as_gated(env):
+    """-8 nibbles under the symmetric range [-7, 7]: an element whose update is zero is never
+    counted (Eq. 4 masks updates), for both update rules; weights and counters equal the oracle's."""
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    out_f, in_f, N = 64, 96, 6
+    rng = np.random.default_rng(4)
+    q = rng.integers(-7, 8, size=(out_f, in_f))
+    q[rng.random((out_f, in_f)) < 0.3] = -8
+    seeds = rng.integers(0, 2 ** 63, size=N, dtype=np.uint64)
+    for fit in (np.zeros(N, np.float32), oracle.normalize_fitness(rng.standard_normal(N).astype(np.float32))):
+        for rule in ("stochastic", "feedback"):
+            ot = oracle.Tensor(wl.pack_int4(q), None, out_f, in_f, 4, 0, -7, 7, 8)
+            dt = u.device_tensor(ot)
+            stats = torch.zeros(2, dtype=torch.int64, device=u.DEV)
+            if rule == "stochastic":
+                qes.update_stochastic_rounding(dt, seeds, fit, 1.0, 2.0, 123, stats=stats)
+                ref = oracle.update_stochastic_rounding(ot, seeds, fit, 1.0, 2.0, 123)
+            else:
+                qes.update(dt, seeds, fit, None, None, 1.0, 2.0, 0.9, stats=stats)
+                ref = oracle.update(ot, seeds, fit, None, None, 1.0, 2.0, 0.9)
+            assert (dt.qweight.cpu().numpy().view(np.uint8) == ot.qweight.view(np.uint8)).all(), rule
+            assert (stats.cpu().numpy().view(np.uint64) == ref).all(), (rule, stats, ref)
+            assert (ref == 0).all() if not fit.any() else ref[1] > 0
+
+
 def test_argument_errors(env):
     torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
     qw, _, qmin, qmax = wl.random_tensor(1, 16, 32, 4, 0)
