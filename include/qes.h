@@ -9,8 +9,8 @@
  *
  * Every entry point returns QES_OK (0) or a negative qes_status; nothing throws. Every check
  * that can refuse a call (arguments, limits, workspace) is made before any device work is enqueued:
- * a call that returns QES_ERR_INVALID_ARG, QES_ERR_UNSUPPORTED or QES_ERR_WORKSPACE has touched no
- * device memory. QES_ERR_HIP reports a failing runtime call and
+ * a call that returns QES_ERR_INVALID_ARG, QES_ERR_UNSUPPORTED, QES_ERR_WORKSPACE or
+ * QES_ERR_TOO_LARGE has touched no device memory. QES_ERR_HIP reports a failing runtime call and
  * may leave earlier launches of the same call on the stream.
  *
  * Device memory the library owns. Entry points that take HOST arrays of seeds and fitnesses stage
@@ -21,7 +21,7 @@
  * recorded behind its last consumer has completed, so with more than 8 calls outstanding the host
  * waits for the oldest (not while holding the library's lock: callers on other streams go on).
  * Because of the first-call allocation and the copy from the pinned slot, these entry points are
- * not for use under stream capture.
+ * not for use under stream capture; qes_update_noalloc is.
  *
  * Passages of the paper each operation implements are cited at its declaration:
  *   §3.2 Eq. 3  stochastically rounded integer perturbation δ
@@ -48,13 +48,15 @@ typedef enum {
     QES_ERR_INVALID_ARG = -1, /* null pointer, bad size, non-finite fitness, sigma out of range ... */
     QES_ERR_UNSUPPORTED = -2, /* a legal request this build has no kernel for (stated per call)   */
     QES_ERR_HIP = -3,         /* a HIP runtime call failed; qes_last_hip_error() has its code      */
-    QES_ERR_WORKSPACE = -4    /* workspace missing or smaller than qes_gemm_workspace_bytes()      */
+    QES_ERR_WORKSPACE = -4,   /* workspace missing or smaller than qes_gemm_workspace_bytes()      */
+    QES_ERR_TOO_LARGE = -5    /* qes_update_noalloc: more records than its fixed scratch holds     */
 } qes_status;
 
 /* Limits of the small HOST arrays. */
 #define QES_MAX_POPULATION 1024 /* N */
 #define QES_MAX_HISTORY 256     /* hist_len */
 #define QES_MAX_BATCH 4096      /* tensors per qes_update_batch / qes_perturbed_qgemm_batch call */
+#define QES_NOALLOC_MAX_RECORDS 16384 /* (hist_len + 1) * N accepted by qes_update_noalloc */
 
 /*
  * One quantised linear weight (App. A.1; INT4 group-scaled and INT8 per-output-channel formats).
@@ -207,6 +209,22 @@ size_t qes_gemm_batch_workspace_bytes(const qes_tensor *tensors, int32_t n_tenso
 int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
                const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha,
                float gamma, uint64_t *stats, void *stream);
+
+/*
+ * qes_update for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc. Same arguments, same results. The (seed, fitness) records do not
+ * go through the staging ring but into a fixed array in the library's device image (256 KiB per
+ * GPU, held until the process ends), written by small kernels that carry the records in their
+ * kernel arguments. The call enqueues kernel launches only: no hipMalloc, hipFree, memcpy or
+ * memset, no wait.
+ *   Limit: (hist_len + 1) * N <= QES_NOALLOC_MAX_RECORDS, else QES_ERR_TOO_LARGE (nothing enqueued).
+ *   All calls on a GPU share that GPU's array, which keeps the last call's records: calls on one
+ *   stream are ordered and safe; calls that overlap on one GPU (different streams without an
+ *   ordering between them, or two host threads) race on it.
+ */
+int qes_update_noalloc(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
+                       const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha,
+                       float gamma, uint64_t *stats, void *stream);
 
 /*
  * The replay loop of Alg. 2 alone: the proxy residual e~ after replaying the history, before the

@@ -59,6 +59,7 @@ def _load():
         "qes_perturbed_qgemm_antithetic": ([tp, vp, vp, i32, f32, vp, i32, vp, i32, vp, sz, vp], i32),
         "qes_gemm_workspace_bytes": ([tp, i32, i32, i32], sz),
         "qes_update": ([tp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
+        "qes_update_noalloc": ([tp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp], i32),
         "qes_perturbed_qgemm_batch": ([vp, i32, vp, vp, i32, f32, vp, i32, vp, i32, vp, sz, vp], i32),
         "qes_perturbed_qgemm_batch_antithetic": ([vp, i32, vp, vp, i32, f32, vp, i32, vp, i32, vp, sz, vp], i32),
         "qes_gemm_batch_workspace_bytes": ([vp, i32, vp, i32, i32, i32], sz),
@@ -88,7 +89,7 @@ def _load():
 
 EXPORTS = ["qes_noise_words", "qes_noise_gauss", "qes_noise_delta", "qes_noise_from_words", "qes_perturbed_qgemm",
            "qes_perturbed_qgemm_antithetic", "qes_gemm_workspace_bytes", "qes_perturbed_qgemm_batch",
-           "qes_perturbed_qgemm_batch_antithetic", "qes_gemm_batch_workspace_bytes", "qes_update", "qes_update_antithetic",
+           "qes_perturbed_qgemm_batch_antithetic", "qes_gemm_batch_workspace_bytes", "qes_update", "qes_update_noalloc", "qes_update_antithetic",
            "qes_update_batch", "qes_update_batch_antithetic",
            "qes_replay_residual", "qes_replay_residual_antithetic", "qes_update_full_residual", "qes_update_full_residual_f16",
            "qes_update_stochastic_rounding", "qes_normalize_fitness",
@@ -246,19 +247,23 @@ def _hist(hist_seeds, hist_fit, N, antithetic=False):
     return hs, hf, int(hs.shape[0])
 
 
-def update(w, seeds_t, fit_t, hist_seeds, hist_fit, sigma, alpha, gamma, stats=None, stream=None, antithetic=False):
+def update(w, seeds_t, fit_t, hist_seeds, hist_fit, sigma, alpha, gamma, stats=None, stream=None, antithetic=False,
+           noalloc=False):
     """In-place Alg. 2 on w.qweight. stats: device int64/uint64 tensor [2] or None. antithetic=True:
-    one seed per pair (N/2 per generation), one fitness per member (qes_update_antithetic)."""
+    one seed per pair (N/2 per generation), one fitness per member (qes_update_antithetic).
+    noalloc=True: qes_update_noalloc (records staged in the library's fixed device array)."""
     seeds_t = _host(seeds_t, np.uint64)
     fit_t = _host(fit_t, np.float32)
     N = int(fit_t.size)
     if seeds_t.size != (N // 2 if antithetic else N) or (antithetic and N % 2):
         raise ValueError("seeds_t and fit_t do not match")
+    if noalloc and antithetic:
+        raise ValueError("qes_update_noalloc has no antithetic form")
     hs, hf, hl = _hist(hist_seeds, hist_fit, N, antithetic)
     d = w.desc()
-    fn = _load().qes_update_antithetic if antithetic else _load().qes_update
-    _check(fn(ctypes.byref(d), _hptr(seeds_t), _hptr(fit_t), _hptr(hs), _hptr(hf), hl, N, sigma, alpha, gamma,
-              _dev_ptr(stats, "stats"), _stream(stream)), "qes_update_antithetic" if antithetic else "qes_update")
+    name = "qes_update_noalloc" if noalloc else ("qes_update_antithetic" if antithetic else "qes_update")
+    _check(getattr(_load(), name)(ctypes.byref(d), _hptr(seeds_t), _hptr(fit_t), _hptr(hs), _hptr(hf), hl, N, sigma,
+                                  alpha, gamma, _dev_ptr(stats, "stats"), _stream(stream)), name)
 
 
 def update_batch(tensors, seeds_t, fit_t, hist_seeds, hist_fit, sigma, alpha, gamma, stats=None, stream=None,

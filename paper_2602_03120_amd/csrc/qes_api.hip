@@ -133,6 +133,50 @@ hipError_t release_slot(Slot *s, bool enqueued, hipStream_t stream)
     return e;
 }
 
+// ---- the entry point that allocates nothing (qes_update_noalloc) keeps its (seed, fitness)
+// records in this fixed device array instead of a ring slot. Each GPU holds its own copy at its
+// own address; host code only ever uses the address hipGetSymbolAddress returned for the current
+// device, never the array's name.
+constexpr uint32_t kScratchRecords = QES_NOALLOC_MAX_RECORDS;
+constexpr int kStageRecords = 240;   // records per staging launch: 3840 bytes of kernel arguments
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kScratchRecords * sizeof(qes::Entry)];
+
+namespace {
+
+struct StageChunk {
+    qes::Entry e[kStageRecords];
+};
+
+// Writes `count` records, passed by value in the kernel arguments, to dst[0..count). Host arrays
+// reach the device this way without a copy engine, a pinned buffer or a memcpy node.
+__global__ __launch_bounds__(256) void stage_records_kernel(const StageChunk chunk, qes::Entry *__restrict__ dst, int count)
+{
+    const int i = threadIdx.x;
+    if (i < count) dst[i] = chunk.e[i];
+}
+
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.
+int scratch_address(qes::Entry **out)
+{
+    int dev = 0;
+    QES_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return QES_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        QES_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return QES_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = (qes::Entry *)g_scratch_ptr[dev];
+    return QES_OK;
+}
+
 int tensor_check(const qes_tensor *w)
 {
     if (!w || !w->qweight) return QES_ERR_INVALID_ARG;
@@ -353,6 +397,55 @@ int update_batch_common(const qes_tensor *tensors, int32_t n_tensors, const uint
     return QES_OK;
 }
 
+// Alg. 2 on one tensor with the records staged through the fixed device array `scratch` by small
+// kernels that carry them in their arguments: only kernel launches are enqueued, nothing is
+// allocated, freed, copied by a copy engine or waited for.
+int update_noalloc(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
+                   const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
+                   uint64_t *stats, void *stream)
+{
+    int rc = update_check(w, seeds_t, fit_t, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, stats, nullptr, 0, false);
+    if (rc != QES_OK) return rc;
+    const int32_t steps = hist_len + 1;
+    const uint64_t n_records = (uint64_t)steps * (uint64_t)N;
+    if (n_records > kScratchRecords) return QES_ERR_TOO_LARGE;
+    const double c64 = (double)alpha / ((double)N * (double)sigma);
+    // every fitness finite, and |u| <= |c|·8·Σ|F| small enough for the float -> int conversion
+    double abs_sum = 0.0;
+    for (int32_t tau = 0; tau < steps; ++tau) {
+        const float *f = tau < hist_len ? hist_fit + (size_t)tau * N : fit_t;
+        for (int32_t i = 0; i < N; ++i) {
+            if (!std::isfinite(f[i])) return QES_ERR_INVALID_ARG;
+            abs_sum += std::fabs((double)f[i]);
+        }
+    }
+    if (std::fabs(c64) * 8.0 * abs_sum >= 1073741824.0) return QES_ERR_INVALID_ARG;
+    qes::Entry *dev_records = nullptr;
+    rc = scratch_address(&dev_records);
+    if (rc != QES_OK) return rc;
+
+    hipStream_t s = (hipStream_t)stream;
+    StageChunk chunk;
+    for (uint64_t r0 = 0; r0 < n_records; r0 += kStageRecords) {
+        const int count = (int)std::min<uint64_t>(kStageRecords, n_records - r0);
+        for (int j = 0; j < count; ++j) {
+            const uint64_t r = r0 + (uint64_t)j;
+            const int32_t tau = (int32_t)(r / (uint64_t)N), i = (int32_t)(r % (uint64_t)N);
+            const uint64_t sd = tau < hist_len ? hist_seeds[(size_t)tau * N + i] : seeds_t[i];
+            const float f = tau < hist_len ? hist_fit[(size_t)tau * N + i] : fit_t[i];
+            uint32_t fb;
+            std::memcpy(&fb, &f, 4);
+            chunk.e[j] = qes::Entry{(uint32_t)sd, (uint32_t)(sd >> 32), fb, 0u};
+        }
+        stage_records_kernel<<<1, 256, 0, s>>>(chunk, dev_records + r0, count);
+        QES_HIP(hipGetLastError());
+    }
+    qes::UpdateArgs a = update_args(w, steps, N, sigma, c64, gamma, stats, nullptr, 0);
+    a.entries = dev_records;
+    QES_HIP(qes::launch_update(a, w->bits, 0, false, s));
+    return QES_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -369,6 +462,7 @@ const char *qes_status_string(int status)
     case QES_ERR_UNSUPPORTED: return "unsupported configuration";
     case QES_ERR_HIP: return "HIP runtime error";
     case QES_ERR_WORKSPACE: return "workspace missing or too small";
+    case QES_ERR_TOO_LARGE: return "request exceeds the fixed scratch of the entry point that allocates nothing";
     default: return "unknown status";
     }
 }
@@ -697,6 +791,13 @@ int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const
 {
     return update_common(w, seeds_t, fit_t, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, stats, nullptr,
                          0, false, stream);
+}
+
+int qes_update_noalloc(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,
+                       const float *hist_fit, int32_t hist_len, int32_t N, float sigma, float alpha, float gamma,
+                       uint64_t *stats, void *stream)
+{
+    return update_noalloc(w, seeds_t, fit_t, hist_seeds, hist_fit, hist_len, N, sigma, alpha, gamma, stats, stream);
 }
 
 int qes_update_antithetic(qes_tensor *w, const uint64_t *pair_seeds_t, const float *fit_t,
