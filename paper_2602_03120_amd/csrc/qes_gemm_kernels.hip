@@ -103,44 +103,50 @@ __device__ __forceinline__ bool block_to_index(uint32_t total, uint32_t &idx)
     return (blockIdx.x >> 3) < per_xcd && idx < total;
 }
 
+// The noise job works in fp32 throughout: base integers, perturbations and gated results are small
+// integers, exact in fp32, so the gate is an add, a median and a select, the 4-bit container clamp
+// of δ is compiled out when sigma <= 1.2 (|sigma*eps| <= 1.2 * 5.77 < 7 cannot reach it), and the
+// bf16 operand is the upper half of the fp32 bit pattern. No int <-> float conversion of δ.
+
 // One pair of elements for both members of an antithetic pair: one draw; the even member gates
-// W + δ, the odd member W - δ (Eq. 4 each). keep_even / keep_odd are all-ones or zero: a member
-// whose perturbation is switched off gates W + 0 = W.
-__device__ __forceinline__ void perturb_pair_both(const int32_t (&w)[2], int32_t (&even)[2], int32_t (&odd)[2], uint32_t k0,
-                                                  uint32_t k1, uint32_t tensor_id, uint32_t pair, float sigma, int32_t qmin,
-                                                  uint32_t qspan, int32_t keep_even, int32_t keep_odd)
+// W + δ, the odd member W - δ (Eq. 4 each). on_even / on_odd are 1 or 0: a member whose
+// perturbation is switched off gates W + 0 = W.
+template <bool CLAMP>
+__device__ __forceinline__ void perturb_pair_both(const float (&w)[2], float (&even)[2], float (&odd)[2], uint32_t k0,
+                                                  uint32_t k1, uint32_t tensor_id, uint32_t pair, float sigma, float qmin,
+                                                  float qmax, float on_even, float on_odd)
 {
-    int32_t d[2];
-    delta_pair(k0, k1, tensor_id, pair, sigma, d[0], d[1]);
+    float d[2];
+    delta_pair_f32<CLAMP>(k0, k1, tensor_id, pair, sigma, d[0], d[1]);
 #pragma unroll
     for (int l = 0; l < 2; ++l) {
-        even[l] = gate(w[l], d[l] & keep_even, qmin, qspan);
-        odd[l] = gate(w[l], (-d[l]) & keep_odd, qmin, qspan);
+        even[l] = gate_f32(w[l], d[l] * on_even, qmin, qmax);
+        odd[l] = gate_f32(w[l], -d[l] * on_odd, qmin, qmax);
     }
 }
 
 // One pair: draw, gate (Eq. 4) in place. SIGN = -1 is the mirrored member of an antithetic pair.
-template <int SIGN>
-__device__ __forceinline__ void perturb_pair(int32_t &w0, int32_t &w1, uint32_t k0, uint32_t k1, uint32_t tensor_id,
-                                             uint32_t pair, float sigma, int32_t qmin, uint32_t qspan)
+template <int SIGN, bool CLAMP>
+__device__ __forceinline__ void perturb_pair(float &w0, float &w1, uint32_t k0, uint32_t k1, uint32_t tensor_id,
+                                             uint32_t pair, float sigma, float qmin, float qmax)
 {
-    int32_t d0, d1;
-    delta_pair(k0, k1, tensor_id, pair, sigma, d0, d1);
-    w0 = gate(w0, SIGN < 0 ? -d0 : d0, qmin, qspan);
-    w1 = gate(w1, SIGN < 0 ? -d1 : d1, qmin, qspan);
+    float d0, d1;
+    delta_pair_f32<CLAMP>(k0, k1, tensor_id, pair, sigma, d0, d1);
+    w0 = gate_f32(w0, SIGN < 0 ? -d0 : d0, qmin, qmax);
+    w1 = gate_f32(w1, SIGN < 0 ? -d1 : d1, qmin, qmax);
 }
 
-// exact bf16 images of two small integers in one dword (low half = first element)
-__device__ __forceinline__ uint32_t pack_bf16x2(int32_t a, int32_t b)
+// exact bf16 images of two small integers held in fp32, in one dword (low half = first element):
+// the upper halves of the two bit patterns
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
 {
-    const uint32_t lo = __float_as_uint((float)a);
-    const uint32_t hi = __float_as_uint((float)b);
-    return (lo >> 16) | (hi & 0xFFFF0000u);
+    return __builtin_amdgcn_perm(__float_as_uint(b), __float_as_uint(a), 0x07060302u);
 }
 
-__device__ __forceinline__ uint32_t pack_i8x4(int32_t a, int32_t b, int32_t c, int32_t d)
+__device__ __forceinline__ uint32_t pack_i8x4(float a, float b, float c, float d)
 {
-    return ((uint32_t)a & 0xFFu) | (((uint32_t)b & 0xFFu) << 8) | (((uint32_t)c & 0xFFu) << 16) | ((uint32_t)d << 24);
+    return ((uint32_t)(int32_t)a & 0xFFu) | (((uint32_t)(int32_t)b & 0xFFu) << 8) | (((uint32_t)(int32_t)c & 0xFFu) << 16) |
+           ((uint32_t)(int32_t)d << 24);
 }
 
 // Position of logical 16-byte chunk `chunk` (0..3) inside the 64-byte LDS row `row`: XOR-swizzled
@@ -174,7 +180,8 @@ struct Gemm {
     const uint16_t *scales[kWR];  // scale rows of this lane's two MFMA row groups
     const uint16_t *job_scales;   // scale row of this lane's noise job
     const char *xg[kP];           // activations of this workgroup's member(s)
-    int32_t keep[2];              // PAIRED: all-ones / zero per member: perturbation on / off
+    float keep[2];                // PAIRED: 1 / 0 per member: perturbation on / off
+    float qmin_f, qmax_f;         // the gate's range, as fp32
     const char *wrow_lane;        // this lane's packed base integers of substep 0 (noise job)
     uint32_t pair0;               // pair index of this lane's half fragment of substep 0
     uint32_t a_off;               // LDS offset of this lane's A fragment of token tile wm
@@ -248,7 +255,7 @@ struct Gemm {
         uint2 d[kP];
     };
 
-    __device__ __forceinline__ uint2 pack_half(const int32_t (&w)[H]) const
+    __device__ __forceinline__ uint2 pack_half(const float (&w)[H]) const
     {
         if (kI8) {
             const uint32_t lo = pack_i8x4(w[0], w[1], w[2], w[3]);
@@ -258,26 +265,27 @@ struct Gemm {
         return make_uint2(lo, H > 2 ? pack_bf16x2(w[H - 2], w[H - 1]) : 0u);
     }
 
-    template <int PERTURB>
+    // PERTURB: 0 base weights, 1 +δ, -1 -δ (mirrored member). CLAMP: the 4-bit container clamp of δ.
+    template <int PERTURB, bool CLAMP>
     __device__ __forceinline__ Halves make_half(int s, uint2 raw, bool zero) const
     {
-        int32_t w[H];
+        float w[H];
 #pragma unroll
         for (int j = 0; j < H; ++j) {
-            if (MODE == kBf16W4) w[j] = ((int32_t)(raw.x << (28 - 4 * j))) >> 28;
-            else w[j] = ((int32_t)((j < 4 ? raw.x : raw.y) << (24 - 8 * (j & 3)))) >> 24;
+            if (MODE == kBf16W4) w[j] = (float)(((int32_t)(raw.x << (28 - 4 * j))) >> 28);
+            else w[j] = (float)(((int32_t)((j < 4 ? raw.x : raw.y) << (24 - 8 * (j & 3)))) >> 24);
         }
         Halves out;
         const uint32_t pair = pair0 + (uint32_t)s * (kSubK / 2);
         if constexpr (PAIRED) {
-            int32_t even[H], odd[H];
+            float even[H], odd[H];
 #pragma unroll
             for (int p = 0; p < H / 2; ++p) {
-                const int32_t wp[2] = {w[2 * p], w[2 * p + 1]};
-                int32_t e2[2] = {wp[0], wp[1]}, o2[2] = {wp[0], wp[1]};
+                const float wp[2] = {w[2 * p], w[2 * p + 1]};
+                float e2[2] = {wp[0], wp[1]}, o2[2] = {wp[0], wp[1]};
                 if (PERTURB != 0)
-                    perturb_pair_both(wp, e2, o2, en.seed_lo, en.seed_hi, a.tensor_id, pair + p, a.sigma, a.qmin, a.qspan,
-                                      keep[0], keep[1]);
+                    perturb_pair_both<CLAMP>(wp, e2, o2, en.seed_lo, en.seed_hi, a.tensor_id, pair + p, a.sigma, qmin_f, qmax_f,
+                                             keep[0], keep[1]);
                 even[2 * p] = e2[0];
                 even[2 * p + 1] = e2[1];
                 odd[2 * p] = o2[0];
@@ -289,8 +297,8 @@ struct Gemm {
             if (PERTURB != 0) {
 #pragma unroll
                 for (int p = 0; p < H / 2; ++p)
-                    perturb_pair<PERTURB>(w[2 * p], w[2 * p + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair + p, a.sigma, a.qmin,
-                                          a.qspan);
+                    perturb_pair<PERTURB, CLAMP>(w[2 * p], w[2 * p + 1], en.seed_lo, en.seed_hi, a.tensor_id, pair + p, a.sigma,
+                                                 qmin_f, qmax_f);
             }
             out.d[0] = pack_half(w);
         }
@@ -324,7 +332,7 @@ struct Gemm {
     // ---- one substep: MFMAs of the fragments of substep s on tile buffer `xbuf`, this wave's half
     // fragment of substep s+1 underneath. PAR is the parity of s: it selects the B-fragment buffer
     // at compile time.
-    template <int PERTURB, int PAR>
+    template <int PERTURB, bool CLAMP, int PAR>
     __device__ __forceinline__ void substep(int s, const char *xbuf, char *xbuf_next)
     {
         const bool has_next = (s + 1) < n_sub;
@@ -361,7 +369,7 @@ struct Gemm {
                     job_zero = ((job_scale_next & 0x7FFFu) == 0);
                 }
             }
-            publish(1 - PAR, make_half<PERTURB>(s + 1, raw, job_zero));
+            publish(1 - PAR, make_half<PERTURB, CLAMP>(s + 1, raw, job_zero));
         }
 
 #pragma unroll
@@ -405,7 +413,7 @@ struct Gemm {
         __syncthreads();
     }
 
-    template <int PERTURB>
+    template <int PERTURB, bool CLAMP>
     __device__ __forceinline__ void pass(int t0, int n0, char *x0, char *x1, uint16_t *const (&yg)[kP],
                                          const float *const (&xs)[kP], const float (&s_row)[kWR])
     {
@@ -432,13 +440,13 @@ struct Gemm {
         __syncthreads();   // the previous pass has finished reading LDS
         issue_tile(0, x0);
         raw_next = n_sub > 1 ? load_raw(1) : make_uint2(0u, 0u);
-        publish(0, make_half<PERTURB>(0, load_raw(0), job_zero));
+        publish(0, make_half<PERTURB, CLAMP>(0, load_raw(0), job_zero));
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
 
         for (int s = 0; s < n_sub; s += 2) {
-            substep<PERTURB, 0>(s, x0, x1);
-            if (s + 1 < n_sub) substep<PERTURB, 1>(s + 1, x1, x0);
+            substep<PERTURB, CLAMP, 0>(s, x0, x1);
+            if (s + 1 < n_sub) substep<PERTURB, CLAMP, 1>(s + 1, x1, x0);
         }
 
 #pragma unroll
@@ -556,17 +564,27 @@ __global__ __launch_bounds__(waves_for(TM, PAIRED) * 64, ((TM >= 512 || (PAIRED 
     // per member: 0 base weights, 1 +δ, 2 -δ (antithetic mirror); per pair: bit 0 = even member
     // perturbed, bit 1 = odd member perturbed
     const uint32_t mode = (a.sigma != 0.0f) ? g.en.fit_bits : 0u;
-    g.keep[0] = (mode & 1u) ? -1 : 0;
-    g.keep[1] = (mode & 2u) ? -1 : 0;
+    g.keep[0] = (mode & 1u) ? 1.0f : 0.0f;
+    g.keep[1] = (mode & 2u) ? 1.0f : 0.0f;
+    g.qmin_f = (float)a.qmin;
+    g.qmax_f = (float)(a.qmin + (int32_t)a.qspan);
+    // |sigma*eps| <= 1.2 * 5.77 < 7: the 4-bit container clamp of δ cannot fire and is compiled out
+    const bool clamp = !(a.sigma <= 1.2f);
 
     for (int t0 = 0; t0 < a.T; t0 += TM) {
         if constexpr (PAIRED) {
-            if (mode != 0u) g.template pass<1>(t0, n0, x0, x1, yg, xs, s_row);
-            else g.template pass<0>(t0, n0, x0, x1, yg, xs, s_row);
+            if (mode == 0u) g.template pass<0, false>(t0, n0, x0, x1, yg, xs, s_row);
+            else if (clamp) g.template pass<1, true>(t0, n0, x0, x1, yg, xs, s_row);
+            else g.template pass<1, false>(t0, n0, x0, x1, yg, xs, s_row);
         } else {
-            if (mode == 1u) g.template pass<1>(t0, n0, x0, x1, yg, xs, s_row);
-            else if (mode == 2u) g.template pass<-1>(t0, n0, x0, x1, yg, xs, s_row);
-            else g.template pass<0>(t0, n0, x0, x1, yg, xs, s_row);
+            if (mode == 0u) g.template pass<0, false>(t0, n0, x0, x1, yg, xs, s_row);
+            else if (clamp) {
+                if (mode == 1u) g.template pass<1, true>(t0, n0, x0, x1, yg, xs, s_row);
+                else g.template pass<-1, true>(t0, n0, x0, x1, yg, xs, s_row);
+            } else {
+                if (mode == 1u) g.template pass<1, false>(t0, n0, x0, x1, yg, xs, s_row);
+                else g.template pass<-1, false>(t0, n0, x0, x1, yg, xs, s_row);
+            }
         }
     }
 }

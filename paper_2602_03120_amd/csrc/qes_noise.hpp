@@ -207,6 +207,14 @@ __device__ __forceinline__ void delta_pair(uint32_t k0, uint32_t k1, uint32_t te
     d1 = delta_of(e1, w.w3, sigma);
 }
 
+// N7 with the operands held in fp32: base and delta are small integers, so base + delta is exact
+// and the range test is a median. Returns base + delta if qmin <= base + delta <= qmax, else base.
+__device__ __forceinline__ float gate_f32(float base, float delta, float qmin, float qmax)
+{
+    const float v = base + delta;
+    return (__builtin_amdgcn_fmed3f(v, qmin, qmax) == v) ? v : base;
+}
+
 // N7 / Alg. 2 gate: v if qmin <= v <= qmax else keep.
 __device__ __forceinline__ int32_t gate(int32_t base, int32_t delta, int32_t qmin, uint32_t qspan)
 {
