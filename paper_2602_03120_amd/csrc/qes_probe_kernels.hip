@@ -141,12 +141,20 @@ __global__ __launch_bounds__(kBlock) void bench_mfma_kernel(int iters, uint32_t 
     sink[(size_t)blockIdx.x * kBlock + threadIdx.x] = acc;
 }
 
+// Plain streaming copy, four 16-byte loads in flight per thread before the four stores.
 __global__ __launch_bounds__(kBlock) void copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
                                                       size_t n16)
 {
     const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += stride)
-        dst[i] = src[i];
+    size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        dst[i] = a;
+        dst[i + stride] = b;
+        dst[i + 2 * stride] = c;
+        dst[i + 3 * stride] = d;
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
 }
 
 inline unsigned blocks_for(uint64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }

@@ -144,11 +144,33 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs args
     for (int j = 0; j < PPT; ++j) P::unpack(raw.pair_bits(j, P::kBytesPerPair), wq[2 * j], wq[2 * j + 1]);
 
     float res[2 * PPT];
+    if constexpr (RMODE == 2 && PPT % 2 == 0) {
+        // 16-byte aligned: the residual is, and pair0 is a multiple of PPT
+        const float4 *src = (const float4 *)(a.residual + (size_t)pair0 * 2);
 #pragma unroll
-    for (int j = 0; j < 2 * PPT; ++j) {
-        if (RMODE == 2) res[j] = a.residual[(size_t)pair0 * 2 + j];
-        else if (RMODE == 3) res[j] = (float)((const _Float16 *)a.residual)[(size_t)pair0 * 2 + j];
-        else res[j] = 0.0f;
+        for (int q = 0; q < PPT / 2; ++q) {
+            const float4 v = src[q];
+            res[4 * q] = v.x;
+            res[4 * q + 1] = v.y;
+            res[4 * q + 2] = v.z;
+            res[4 * q + 3] = v.w;
+        }
+    } else if constexpr (RMODE == 3 && PPT % 4 == 0) {
+        typedef __attribute__((ext_vector_type(8))) _Float16 half8;
+        const half8 *src = (const half8 *)((const _Float16 *)a.residual + (size_t)pair0 * 2);
+#pragma unroll
+        for (int q = 0; q < PPT / 4; ++q) {
+            const half8 v = src[q];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) res[8 * q + j] = (float)v[j];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 2 * PPT; ++j) {
+            if (RMODE == 2) res[j] = a.residual[(size_t)pair0 * 2 + j];
+            else if (RMODE == 3) res[j] = (float)((const _Float16 *)a.residual)[(size_t)pair0 * 2 + j];
+            else res[j] = 0.0f;
+        }
     }
 
     uint32_t changed = 0, gated = 0;
@@ -245,13 +267,30 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs args
     }
     if (active && (RMODE == 1 || RMODE == 2)) {
         float *out = a.residual + (size_t)pair0 * 2;
+        if constexpr (PPT % 2 == 0) {
 #pragma unroll
-        for (int j = 0; j < 2 * PPT; ++j) out[j] = res[j];
+            for (int q = 0; q < PPT / 2; ++q)
+                ((float4 *)out)[q] = make_float4(res[4 * q], res[4 * q + 1], res[4 * q + 2], res[4 * q + 3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2 * PPT; ++j) out[j] = res[j];
+        }
     }
     if (active && RMODE == 3) {
         _Float16 *out = (_Float16 *)a.residual + (size_t)pair0 * 2;
+        if constexpr (PPT % 4 == 0) {
+            typedef __attribute__((ext_vector_type(8))) _Float16 half8;
 #pragma unroll
-        for (int j = 0; j < 2 * PPT; ++j) out[j] = (_Float16)fminf(fmaxf(res[j], -65504.0f), 65504.0f);
+            for (int q = 0; q < PPT / 4; ++q) {
+                half8 v;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = (_Float16)fminf(fmaxf(res[8 * q + j], -65504.0f), 65504.0f);
+                ((half8 *)out)[q] = v;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2 * PPT; ++j) out[j] = (_Float16)fminf(fmaxf(res[j], -65504.0f), 65504.0f);
+        }
     }
     if (RMODE != 1) {
         if (changed) {   // zero in the lanes past the end
@@ -281,9 +320,32 @@ __global__ __launch_bounds__(kBlock, 8) void update_kernel(const UpdateArgs args
 constexpr int kPairsPerThread = 1;
 constexpr int kMembersAtATime = 4;
 
+// One Alg. 1 step on a stored residual with a small population is the one launch on this path
+// where memory traffic is comparable to the noise work (N draws per element against 5 to 9 bytes):
+// there a thread owns four pairs (a dword of INT4 or two of INT8, 32 bytes of fp32 or 16 bytes of
+// binary16 residual, moved with vector loads and stores) and regenerates one member's draws for
+// all four at a time. Same arithmetic per element, same results.
+constexpr int kWidePairsPerThread = 4;
+constexpr int kWideMaxPopulation = 8;
+
+template <int BITS, int RMODE>
+hipError_t launch_wide_variant(const UpdateArgs &a, hipStream_t s)
+{
+    constexpr int P = kWidePairsPerThread;
+    const uint64_t threads = a.n_pairs / P;
+    const unsigned blocks = (unsigned)((threads + kBlock - 1) / kBlock);
+    if (!(a.sigma <= 1.2f)) update_kernel<BITS, P, 1, RMODE, true, false, false><<<blocks, kBlock, 0, s>>>(a);
+    else update_kernel<BITS, P, 1, RMODE, false, false, false><<<blocks, kBlock, 0, s>>>(a);
+    return hipGetLastError();
+}
+
 template <int BITS, int RMODE>
 hipError_t launch_variant(const UpdateArgs &a, bool antithetic, hipStream_t s)
 {
+    if constexpr (RMODE == 2 || RMODE == 3) {
+        if (!antithetic && a.N <= kWideMaxPopulation && a.n_pairs % kWidePairsPerThread == 0)
+            return launch_wide_variant<BITS, RMODE>(a, s);
+    }
     const uint64_t threads = a.n_pairs / kPairsPerThread;
     const unsigned blocks = (unsigned)((threads + kBlock - 1) / kBlock);
     // |sigma*eps| <= 1.2 * 5.77 < 7: the 4-bit container clamp cannot fire and is compiled out

@@ -18,7 +18,10 @@ def env(oracle):
 
 
 @pytest.mark.parametrize("bits,out_f,in_f,N,steps", [(4, 256, 256, 8, 6), (8, 1024, 1024, 5, 3), (4, 33, 70, 30, 4),
-                                                     (4, 2048, 1024, 4, 2), (4, 1024, 4096, 3, 2)])
+                                                     (4, 2048, 1024, 4, 2), (4, 1024, 4096, 3, 2),
+                                                     # four pairs per thread (N <= 8): a ragged last wave,
+                                                     # INT8; and a pair count that is not a multiple of 4
+                                                     (4, 5, 72, 2, 3), (8, 9, 136, 3, 3), (8, 7, 34, 2, 3)])
 def test_steps_match_oracle(env, bits, out_f, in_f, N, steps):
     torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
     qw, _, qmin, qmax = wl.random_tensor(500 + out_f, out_f, in_f, bits, 0)
@@ -78,7 +81,8 @@ def test_full_residual_argument_errors(env):
 
 @pytest.mark.parametrize("bits,out_f,in_f,N,steps,alpha", [(4, 256, 256, 8, 6, 1.5), (8, 1024, 1024, 5, 3, 1.5),
                                                            (4, 33, 70, 30, 4, 1.5), (4, 2048, 1024, 4, 2, 1.5),
-                                                           (4, 1024, 4096, 3, 2, 1.5),
+                                                           (4, 1024, 4096, 3, 2, 1.5), (4, 5, 72, 2, 3, 1.5),
+                                                           (8, 9, 136, 3, 3, 1.5), (8, 7, 34, 2, 3, 1.5),
                                                            (4, 64, 64, 6, 3, 3e6)])   # huge steps: gated residuals saturate
 def test_half_precision_residual_steps_match_oracle(env, bits, out_f, in_f, N, steps, alpha):
     """The residual held as binary16 (Alg. 1's initialisation): weights, residual bit patterns and
