@@ -48,7 +48,12 @@ HBM_PEAK_GBPS = 8000.0
 # (config, N, K) they were measured on and are omitted for anything else.
 #   traffic_bytes: FETCH_SIZE + WRITE_SIZE per launch, scaled by the same counters on the plain
 #                  copy issued below;  valu_insts: SQ_INSTS_VALU (wave instructions) per launch.
-MEASURED_PER_LAUNCH = {}
+MEASURED_PER_LAUNCH = {
+    (5, 32, 32): {"traffic_bytes": (53443.0 * 2 + 1307.05) * 1024, "valu_insts": 1.96147e11},
+    (4, 64, 32): {"traffic_bytes": (23175.7 * 2 + 0.09) * 1024, "valu_insts": 8.37747e10},
+    (3, 30, 16): {"traffic_bytes": (11559.9 * 2 + 382.56) * 1024, "valu_insts": 2.03498e10},
+    (2, 30, 8): {"traffic_bytes": (3296.94 * 2 + 44.30) * 1024, "valu_insts": 3.01387e9},
+}
 HEADLINE_CONFIG = 5
 
 
@@ -111,7 +116,8 @@ class Workload:
         self.params = n_layers * sum(l.out_features * l.in_features for l in cfg.linears)
 
 
-def run_steps(torch, qes, work, steps, warmup, anti=False, per_tensor_gemm=False, per_tensor_update=False):
+def run_steps(torch, qes, work, steps, warmup, anti=False, per_tensor_gemm=False, per_tensor_update=False,
+              progress_lines=True):
     """warmup untimed steps, then `steps` timed ones bracketed by synchronisations. Returns the wall
     time per step and the HIP-event times (recorded on the launch stream) of the evaluation pass
     and of every update launch."""
@@ -160,12 +166,21 @@ def run_steps(torch, qes, work, steps, warmup, anti=False, per_tensor_gemm=False
         if timed:
             gemm_events.append((g0, g1))
 
+    # progress goes to stderr (one line per step; the host runs at most a few launches ahead of
+    # the device, so the lines follow the real progress): a run of minutes must not look hung
+    def progress(what, s):
+        if progress_lines and work.params > 100_000_000:     # long steps only: short ones are not perturbed
+            print("bench.py: config %d %s step %d of %d enqueued" % (cfg.index, what, s + 1, total_steps), file=sys.stderr,
+                  flush=True)
+
     for s in range(warmup):
         step(s, False)
+        progress("warm-up", s)
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
     for s in range(warmup, total_steps):
         step(s, True)
+        progress("timed", s)
     torch.cuda.synchronize()
     t_end = time.perf_counter()
     upd_ms_by_li = {}
@@ -449,6 +464,8 @@ def main():
     }
 
     if not args.no_extras:
+        print("bench.py: timed steps done (%.1f ms per step); measuring ceilings and the other entry points" % ms_per_step,
+              file=sys.stderr, flush=True)
         ceilings = measure_ceilings(torch, qes, dev)
         out["ceilings"] = ceilings
         # the binding resource, against what the same generator sustains with nothing else to do
@@ -474,6 +491,7 @@ def main():
             parts["configs"] = others
 
     if not args.no_cpu_baseline and not anti:
+        print("bench.py: timing the CPU oracle on a sample of the workload", file=sys.stderr, flush=True)
         out["cpu_baseline"] = cpu_baseline(cfg, member_tokens)
     print(json.dumps(out))
 
