@@ -241,15 +241,15 @@ def measure_ceilings(torch, qes, dev):
     this run: Philox words/s and full pair draws/s (four chains per thread, eight waves per SIMD, no
     memory), bf16 and int8 matrix instructions on register operands, a plain streaming copy."""
     out = {}
-    n_threads = 256 * 4 * 8 * 64 * 4          # 4 rounds of 8 waves per SIMD
+    n_threads = 256 * 4 * 8 * 64 * 2          # two full rounds of 8 waves per SIMD
     sink = torch.empty(n_threads, dtype=torch.int32, device=dev)
-    iters = 512
-    ms = time_call(torch, lambda: qes.bench_noise(0, n_threads, iters, 1.0, sink), 5)
+    iters = 8192                              # tens of milliseconds per launch: clocks settle, the tail is small
+    ms = time_call(torch, lambda: qes.bench_noise(0, n_threads, iters, 1.0, sink), 3, warm=2)
     out["philox_words_per_s"] = 4.0 * n_threads * iters / (ms * 1e-3)
-    ms = time_call(torch, lambda: qes.bench_noise(1, n_threads, iters, 1.0, sink), 5)
+    ms = time_call(torch, lambda: qes.bench_noise(1, n_threads, iters, 1.0, sink), 3, warm=2)
     out["pair_draws_per_s"] = n_threads * iters / (ms * 1e-3)
     out["draws_per_s"] = 2.0 * out["pair_draws_per_s"]
-    n_blocks, m_iters, tiles = 256 * 8, 4096, 8
+    n_blocks, m_iters, tiles = 256 * 8, 16384, 8
     msink = torch.empty(n_blocks * 256, dtype=torch.int32, device=dev)
     ms = time_call(torch, lambda: qes.bench_mfma(0, n_blocks, m_iters, msink), 5)
     out["mfma_bf16_flop_per_s"] = n_blocks * 4.0 * m_iters * tiles * 16384.0 / (ms * 1e-3)
@@ -435,7 +435,9 @@ def main():
         # issued vector instructions (SQ_INSTS_VALU, 64 lanes each) against the same peak: what the
         # compiled kernel actually occupies the VALUs with, as opposed to the hand count above
         "issue_frac": counters["valu_insts"] * 64.0 / (dom_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS if counters else None,
-        "valu_insts_per_pair_draw": counters["valu_insts"] / (dom_elems / 2.0 * (cfg.K + 1) * draws_n) if counters else None,
+        # wave instructions per wave-wide pair draw (64 lanes draw 64 pairs at a time)
+        "valu_insts_per_pair_draw": counters["valu_insts"] / (dom_elems / 2.0 * (cfg.K + 1) * draws_n / 64.0)
+        if counters else None,
         "draws_per_s": dom_elems * (cfg.K + 1) * draws_n / (dom_ms * 1e-3),
     }
 
