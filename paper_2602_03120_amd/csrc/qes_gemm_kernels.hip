@@ -150,8 +150,12 @@ __device__ __forceinline__ uint32_t pack_i8x4(float a, float b, float c, float d
 }
 
 // Position of logical 16-byte chunk `chunk` (0..3) inside the 64-byte LDS row `row`: XOR-swizzled
-// with row bits 2..3 so that the 16 rows one b128 fragment read touches spread over all banks.
-__device__ __forceinline__ int swizzle(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
+// with row bits 1..2. A b128 read serves eight consecutive lanes (eight rows, one chunk each) per
+// pass of the 128-byte-wide LDS; two rows share a 128-byte line, so rows 2i and 2i+1 take the two
+// halves and the swizzle gives the four row pairs four different chunks: all 32 banks, once each.
+// (SQ_LDS_BANK_CONFLICT of a config-5 layer: 3.3e8 with row bits 2..3, 1.1e8 with bits 1..2, the rest
+// being the 8-byte fragment writes at a 16-byte lane stride.)
+__device__ __forceinline__ int swizzle(int row, int chunk) { return chunk ^ ((row >> 1) & 3); }
 
 template <int MODE, int TM, bool PAIRED>
 struct Gemm {
