@@ -216,7 +216,8 @@ int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const
  * go through the staging ring but into a fixed array in the library's device image (256 KiB per
  * GPU, held until the process ends), written by small kernels that carry the records in their
  * kernel arguments. The call enqueues kernel launches only: no hipMalloc, hipFree, memcpy or
- * memset, no wait.
+ * memset, no wait; a captured call replays with the records it was captured with. The first call
+ * on a device looks up the array's device address (hipGetSymbolAddress): make it outside a capture.
  *   Limit: (hist_len + 1) * N <= QES_NOALLOC_MAX_RECORDS, else QES_ERR_TOO_LARGE (nothing enqueued).
  *   All calls on a GPU share that GPU's array, which keeps the last call's records: calls on one
  *   stream are ordered and safe; calls that overlap on one GPU (different streams without an

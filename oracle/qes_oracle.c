@@ -542,7 +542,7 @@ int oracle_replay_residual(const oracle_tensor *w, const uint64_t *hist_seeds, c
 
 /*
  * Alg. 2 in full: replay the history, then apply the new population's step to the weights in
- * place. stats (may be NULL): stats[0] += number of elements whose weight changed, stats[1] +=
+ * place (all rows, or the distinct rows listed in `rows`: a row listed twice would be updated twice). stats (may be NULL): stats[0] += number of elements whose weight changed, stats[1] +=
  * number of elements whose non-zero rounded update was masked by the gate (final step only; Eq. 4
  * masks updates, so a zero update is never counted, whatever the stored weight is).
  */

@@ -79,7 +79,8 @@ static int exercise(int bits, int group, int out_f, int in_f, int N, int T, int 
     float *rew = malloc((size_t)N * 4), *fit = malloc((size_t)(K + 1) * N * 4);
     float *res = malloc(elems * 4), *u = malloc(elems * 4);
     uint16_t *res16 = malloc(elems * 2);
-    int32_t rows[3] = { 0, out_f / 2, out_f - 1 };
+    int32_t rows[3] = { 0, out_f / 2, out_f - 1 };   /* distinct rows only: each listed row is updated once */
+    const int32_t n_sel = out_f >= 3 ? 3 : 1;
     if (!qw || !qw0 || !sc || !x || !y || !seeds || !rew || !fit || !res || !u || !res16) return 3;
     for (size_t i = 0; i < wbytes; ++i) {
         if (bits == 4) {
@@ -104,7 +105,7 @@ static int exercise(int bits, int group, int out_f, int in_f, int N, int T, int 
     CHECK(oracle_perturbed_qgemm(&w, seeds, NULL, N, 1.0f, x, T, y, 0, NULL, 0, 0));
     mix(y, (size_t)N * T * out_f * 2);
     memset(y, 0, (size_t)N * T * out_f * 2);
-    CHECK(oracle_perturbed_qgemm(&w, seeds, NULL, N, 1.0f, x, T, y, 0, rows, 3, 0));
+    CHECK(oracle_perturbed_qgemm(&w, seeds, NULL, N, 1.0f, x, T, y, 0, rows, n_sel, 0));
     mix(y, (size_t)N * T * out_f * 2);
     if ((N & 1) == 0) {
         memset(y, 0, (size_t)N * T * out_f * 2);
@@ -120,7 +121,7 @@ static int exercise(int bits, int group, int out_f, int in_f, int N, int T, int 
     CHECK(oracle_replay_residual(&w, seeds, fit, K, N, 1.0f, 1.5f, 0.9f, res, NULL, 0, 0));
     mix(res, elems * 4);
     memset(res, 0, elems * 4);
-    CHECK(oracle_replay_residual(&w, seeds, fit, K, N, 1.0f, 1.5f, 0.9f, res, rows, 3, 0));
+    CHECK(oracle_replay_residual(&w, seeds, fit, K, N, 1.0f, 1.5f, 0.9f, res, rows, n_sel, 0));
     mix(res, elems * 4);
     CHECK(oracle_aggregate(&w, seeds, fit, N, 1.0f, u, 0));
     mix(u, elems * 4);
@@ -128,7 +129,7 @@ static int exercise(int bits, int group, int out_f, int in_f, int N, int T, int 
     CHECK(oracle_update(&w, seeds + (size_t)K * N, fit + (size_t)K * N, seeds, fit, K, N, 1.0f, 1.5f, 0.9f, stats, NULL, 0, 0));
     mix(qw, wbytes);
     memcpy(qw, qw0, wbytes);
-    CHECK(oracle_update(&w, seeds + (size_t)K * N, fit + (size_t)K * N, seeds, fit, K, N, 1.0f, 1.5f, 0.9f, stats, rows, 3, 0));
+    CHECK(oracle_update(&w, seeds + (size_t)K * N, fit + (size_t)K * N, seeds, fit, K, N, 1.0f, 1.5f, 0.9f, stats, rows, n_sel, 0));
     mix(qw, wbytes);
     if ((N & 1) == 0) {
         memcpy(qw, qw0, wbytes);
@@ -152,7 +153,7 @@ static int exercise(int bits, int group, int out_f, int in_f, int N, int T, int 
     mix(res16, elems * 2);
     memcpy(qw, qw0, wbytes);
     CHECK(oracle_update_stochastic_rounding(&w, seeds, fit, N, 1.0f, 3.0f, 0x123456789ull, stats, NULL, 0));
-    CHECK(oracle_update_stochastic_rounding(&w, seeds, fit, N, 1.0f, 3.0f, 0x123456789ull, stats, rows, 3));
+    CHECK(oracle_update_stochastic_rounding(&w, seeds, fit, N, 1.0f, 3.0f, 0x123456789ull, stats, rows, n_sel));
     mix(qw, wbytes);
     mix(stats, sizeof stats);
     free(qw); free(qw0); free(sc); free(x); free(y); free(seeds); free(rew); free(fit); free(res); free(u); free(res16);

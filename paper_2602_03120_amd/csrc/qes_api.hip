@@ -639,7 +639,12 @@ size_t qes_gemm_batch_workspace_bytes(const qes_tensor *tensors, int32_t n_tenso
                                       int32_t T, int32_t act_mode)
 {
     if (!tensors || !x || n_tensors <= 0 || n_tensors > QES_MAX_BATCH || act_mode != 1 || N <= 0 || T <= 0) return 0;
-    std::vector<int32_t> which((size_t)n_tensors);
+    std::vector<int32_t> which;
+    try {
+        which.resize((size_t)n_tensors);
+    } catch (...) {
+        return 0;
+    }
     const int32_t n_distinct = distinct_inputs(tensors, n_tensors, x, which.data());
     size_t total = 0;
     for (int32_t d = 0; d < n_distinct; ++d)
@@ -772,8 +777,12 @@ int qes_perturbed_qgemm_batch(const qes_tensor *tensors, int32_t n_tensors, cons
                               const uint8_t *perturb_mask, int32_t N, float sigma, const void *const *x, int32_t T,
                               void *const *y, int32_t act_mode, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return gemm_batch_common(tensors, n_tensors, seeds, perturb_mask, N, sigma, x, T, y, act_mode, workspace,
-                             workspace_bytes, false, stream);
+    try {
+        return gemm_batch_common(tensors, n_tensors, seeds, perturb_mask, N, sigma, x, T, y, act_mode, workspace,
+                                 workspace_bytes, false, stream);
+    } catch (...) {   // host memory for the launch tables could not be obtained; nothing was enqueued
+        return QES_ERR_UNSUPPORTED;
+    }
 }
 
 int qes_perturbed_qgemm_batch_antithetic(const qes_tensor *tensors, int32_t n_tensors, const uint64_t *pair_seeds,
@@ -781,8 +790,12 @@ int qes_perturbed_qgemm_batch_antithetic(const qes_tensor *tensors, int32_t n_te
                                          int32_t T, void *const *y, int32_t act_mode, void *workspace,
                                          size_t workspace_bytes, void *stream)
 {
-    return gemm_batch_common(tensors, n_tensors, pair_seeds, perturb_mask, N, sigma, x, T, y, act_mode, workspace,
-                             workspace_bytes, true, stream);
+    try {
+        return gemm_batch_common(tensors, n_tensors, pair_seeds, perturb_mask, N, sigma, x, T, y, act_mode, workspace,
+                                 workspace_bytes, true, stream);
+    } catch (...) {
+        return QES_ERR_UNSUPPORTED;
+    }
 }
 
 int qes_update(qes_tensor *w, const uint64_t *seeds_t, const float *fit_t, const uint64_t *hist_seeds,

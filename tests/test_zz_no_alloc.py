@@ -68,3 +68,41 @@ def test_no_history_and_limit(env):
     qes.update(t, seeds[K], fit[K], seeds[:K], fit[:K], 1.0, 4.0, 0.9, noalloc=True)
     qes.update(t2, seeds[K], fit[K], seeds[:K], fit[:K], 1.0, 4.0, 0.9)
     assert torch.equal(t.qweight, t2.qweight)
+
+
+def test_captured_in_a_hip_graph_and_replayed(env):
+    """The call enqueues kernel launches only, so it can be captured: the records travel in the
+    captured kernels' arguments. Three replays, with eager work and synchronisations in between, must
+    leave the weights where three eager calls of qes_update leave them (the update is in place, so
+    replay k starts from the weights replay k-1 produced)."""
+    torch, qes, u = env["torch"], env["qes"], env["u"]
+    rng = np.random.default_rng(21)
+    out_f, in_f, N, K = 64, 192, 12, 5
+    qw, _, qmin, qmax = wl.random_tensor(21, out_f, in_f, 4, 0)
+    seeds = rng.integers(0, 2 ** 63, size=(K + 1, N), dtype=np.uint64)
+    fit = np.stack([qes.normalize_fitness(rng.standard_normal(N).astype(np.float32)) for _ in range(K + 1)])
+    eager = qes.Tensor(u.to_dev(qw), None, out_f, in_f, 4, 0, qmin, qmax, 4)
+    graphed = qes.Tensor(u.to_dev(qw), None, out_f, in_f, 4, 0, qmin, qmax, 4)
+    warm = qes.Tensor(u.to_dev(qw), None, out_f, in_f, 4, 0, qmin, qmax, 4)
+    # the first call on a device looks up the fixed array's address: outside the capture
+    qes.update(warm, seeds[K], fit[K], seeds[:K], fit[:K], 1.0, 1.5, 0.9, noalloc=True)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        qes.update(graphed, seeds[K], fit[K], seeds[:K], fit[:K], 1.0, 1.5, 0.9, noalloc=True, stream=side.cuda_stream)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    assert torch.equal(graphed.qweight.cpu(), torch.from_numpy(qw))        # capturing ran nothing
+    for k in range(3):
+        graph.replay()
+        qes.update(eager, seeds[K], fit[K], seeds[:K], fit[:K], 1.0, 1.5, 0.9)
+        # another call through the same fixed array between the replays: the graph carries its own records
+        other = qes.Tensor(u.to_dev(qw), None, out_f, in_f, 4, 0, qmin, qmax, 9)
+        qes.update(other, seeds[0], fit[0], None, None, 1.0, 1.5, 0.9, noalloc=True)
+        torch.cuda.synchronize()
+        assert torch.equal(graphed.qweight, eager.qweight), k
+    assert not torch.equal(graphed.qweight.cpu(), torch.from_numpy(qw))
