@@ -475,6 +475,15 @@ def main():
         parts["gemm_frac_of_measured_noise_ceiling"] = parts["gemm_draws_per_s"] / ceilings["draws_per_s"]
         parts.update(measure_update_variants(torch, qes, work, dev))
         if not overridden and not anti and cfg.index == HEADLINE_CONFIG:
+            # the same workload with antithetic perturbation pairs (App. A.1: N/2 seeds, members 2j and
+            # 2j+1 on +δ and -δ): half the noise work; reported beside the headline, not as it
+            ra = run_steps(torch, qes, work, 2, 1, anti=True)
+            pa = part_figures(cfg, work, ra, True, False)
+            parts["antithetic_pairs"] = {"ms_per_step": ra["ms_per_step"],
+                                         "member_tokens_per_s": member_tokens / (ra["ms_per_step"] * 1e-3),
+                                         "gemm_ms_per_pass": pa["gemm_ms_per_pass"],
+                                         "update_ms_per_step": pa["update_ms_per_step"],
+                                         "note": "2 steps after 1 warm-up, same tensors and inputs"}
             del work
             torch.cuda.empty_cache()
             others = {}
