@@ -166,10 +166,14 @@ def run_steps(torch, qes, work, steps, warmup, anti=False, per_tensor_gemm=False
         if timed:
             gemm_events.append((g0, g1))
 
-    # progress goes to stderr (one line per step; the host runs at most a few launches ahead of
-    # the device, so the lines follow the real progress): a run of minutes must not look hung
+    # progress goes to stderr (the host runs at most a few launches ahead of the device, so the
+    # lines follow the real progress): a run of minutes must not look hung
+    last_line = [time.perf_counter()]
+
     def progress(what, s):
-        if progress_lines and work.params > 100_000_000:     # long steps only: short ones are not perturbed
+        # about one line a minute, long runs only
+        if progress_lines and time.perf_counter() - last_line[0] > 45.0:
+            last_line[0] = time.perf_counter()
             print("bench.py: config %d %s step %d of %d enqueued" % (cfg.index, what, s + 1, total_steps), file=sys.stderr,
                   flush=True)
 
