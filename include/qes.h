@@ -73,8 +73,8 @@ typedef enum {
  *            bits=4: within [-8,7]; bits=8: within [-128,127].
  *   tensor_id  caller-assigned, distinct per tensor; enters the Philox counter so that two
  *            tensors never share noise.
- * in_features must be even. out_features*in_features must be below 2^33 (the pair index is kept
- * in 32 bits inside the tensor kernels).
+ * in_features must be even. out_features*in_features must not exceed 2^33 - 4096 (pair and thread
+ * indices are kept in 32 bits inside the tensor kernels); larger tensors are QES_ERR_UNSUPPORTED.
  */
 typedef struct {
     void *qweight;

@@ -188,7 +188,9 @@ int tensor_check(const qes_tensor *w)
     if (w->bits == 4 && (w->qmin < -8 || w->qmax > 7)) return QES_ERR_INVALID_ARG;
     if (w->bits == 8 && (w->qmin < -128 || w->qmax > 127)) return QES_ERR_INVALID_ARG;
     if (((uintptr_t)w->qweight & 15u) != 0) return QES_ERR_INVALID_ARG;
-    if ((uint64_t)w->out_features * (uint64_t)w->in_features >= (1ull << 33)) return QES_ERR_UNSUPPORTED;
+    // the tensor kernels number threads and pairs in 32 bits: the last, partly filled workgroup of
+    // the largest tensor must not wrap
+    if ((uint64_t)w->out_features * (uint64_t)w->in_features > (1ull << 33) - 4096u) return QES_ERR_UNSUPPORTED;
     return QES_OK;
 }
 

@@ -50,6 +50,34 @@ def test_normalize_fitness_against_numpy():
     assert (qes.normalize_fitness(np.float32([1e-20, 1e-20, 1e-20])) == 0).all()
 
 
+def test_argument_checks_precede_any_gpu_call():
+    """Refusals that depend on the arguments alone are returned before the first HIP call, so they
+    can be observed without a GPU (the device pointer below is never dereferenced): a tensor above
+    the element limit, a bad width, a population above the limit, more records than the entry point
+    that allocates nothing holds."""
+    import paper_2602_03120_amd.binding as b
+    lib = b._load()
+    seeds = np.zeros(2048, dtype=np.uint64)
+    fit = np.zeros(2048, dtype=np.float32)
+
+    def call(name, out_f, in_f, bits=4, N=4, hist_len=0):
+        d = b._QesTensor(4096, None, out_f, in_f, bits, 0, -8 if bits == 4 else -127, 7 if bits == 4 else 127, 1)
+        hs = np.zeros((max(hist_len, 1), N), dtype=np.uint64)
+        hf = np.zeros((max(hist_len, 1), N), dtype=np.float32)
+        return getattr(lib, name)(ctypes.byref(d), seeds.ctypes.data, fit.ctypes.data, hs.ctypes.data, hf.ctypes.data,
+                                  hist_len, N, 1.0, 0.5, 0.9, None, None)
+
+    assert call("qes_update", 65536, 131072) == -2            # 2^33 elements
+    assert call("qes_update", 65537, 131070) == -2            # 2^33 - 4096 < elements < 2^33
+    assert call("qes_update", 64, 64, bits=5) == -1
+    assert call("qes_update", 64, 63) == -1                   # odd in_features
+    assert call("qes_update", 64, 64, N=1025) == -1
+    assert call("qes_update", 64, 64, hist_len=257) == -1
+    assert call("qes_update_noalloc", 64, 64, N=1024, hist_len=16) == -5      # 17 * 1024 records > 16384
+    assert call("qes_update_noalloc", 64, 64, N=1025) == -1
+    assert "scratch" in b.status_string(-5) or "exceeds" in b.status_string(-5)
+
+
 def test_product_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2602_03120_amd")
     for dirpath, _, files in os.walk(pkg):
