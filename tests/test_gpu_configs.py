@@ -10,6 +10,8 @@ the counter-based noise makes exact: first row, last row and seeded random rows 
 every layer, plus the whole first layer of config 3 for the update. Where the oracle follows only
 some rows, its copy of the other rows goes stale and is never read.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -226,6 +228,46 @@ def test_config_3_layer_0_updated_in_full(env):
     ref_stats = np.zeros(2, dtype=np.uint64)
     for ot, dt, spec in zip(ots, dts, cfg.linears):
         print("config 3 layer 0 %s" % spec.name, flush=True)
+        ref_stats = oracle.update(ot, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha,
+                                  cfg.gamma, stats=ref_stats)
+        assert (dt.qweight.cpu().numpy() == ot.qweight).all(), spec.name
+    assert (stats.cpu().numpy().view(np.uint64) == ref_stats).all() and ref_stats[0] > 0
+
+
+@pytest.mark.skipif(os.environ.get("QES_LONG_TESTS") != "1",
+                    reason="five minutes of oracle time: run with QES_LONG_TESTS=1")
+def test_config_5_layer_0_in_full(env):
+    """Every output and every element of the headline configuration's first layer (seven tensors,
+    218 M parameters, N=32, T=128, K=32): the batched GEMM against the oracle on all columns, all
+    members and tokens, then the batched update with the full window against the oracle's update of
+    all rows, counters included."""
+    torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
+    cfg = wl.CONFIGS[5]
+    seeds = wl.make_seeds(cfg, cfg.K + 1)
+    fits = np.stack([oracle.normalize_fitness(r) for r in wl.make_rewards(cfg, cfg.K + 1)])
+    ots = [oracle.Tensor(wl.make_qweight(cfg, 0, li), wl.make_scales(cfg, 0, li), spec.out_features, spec.in_features,
+                         cfg.bits, cfg.group_size, cfg.qmin, cfg.qmax, cfg.tensor_id(0, li))
+           for li, spec in enumerate(cfg.linears)]
+    dts = [u.device_tensor(ot) for ot in ots]
+    xs_host = {}
+    for spec in cfg.linears:
+        if spec.x_key not in xs_host:
+            xs_host[spec.x_key] = wl.make_activations(cfg, spec.x_key, spec.in_features)
+    xs_dev = {k: u.to_dev(v).view(torch.bfloat16) for k, v in xs_host.items()}
+    xs = [xs_dev[spec.x_key] for spec in cfg.linears]
+    ys = [torch.empty((cfg.N, cfg.T, spec.out_features), dtype=torch.bfloat16, device=u.DEV) for spec in cfg.linears]
+    qes.perturbed_qgemm_batch(dts, seeds[cfg.K], cfg.sigma, xs, ys)
+    for li, spec in enumerate(cfg.linears):
+        print("config 5 layer 0 GEMM %s" % spec.name, flush=True)
+        ref = oracle.perturbed_qgemm(ots[li], seeds[cfg.K], cfg.sigma, xs_host[spec.x_key])
+        ok, worst = u.bf16_close(ys[li].view(torch.int16).cpu().numpy().view(np.uint16), ref)
+        assert ok, (spec.name, worst)
+    stats = torch.zeros(2, dtype=torch.int64, device=u.DEV)
+    qes.update_batch(dts, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha, cfg.gamma,
+                     stats=stats)
+    ref_stats = np.zeros(2, dtype=np.uint64)
+    for ot, dt, spec in zip(ots, dts, cfg.linears):
+        print("config 5 layer 0 update %s" % spec.name, flush=True)
         ref_stats = oracle.update(ot, seeds[cfg.K], fits[cfg.K], seeds[:cfg.K], fits[:cfg.K], cfg.sigma, cfg.alpha,
                                   cfg.gamma, stats=ref_stats)
         assert (dt.qweight.cpu().numpy() == ot.qweight).all(), spec.name
