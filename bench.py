@@ -465,6 +465,13 @@ def main():
                    % ("GEMM: one call per %s, update: one call per %s"
                       % ("tensor" if args.per_tensor_gemm else "layer", "tensor" if args.per_tensor_update else "layer")),
                    "antithetic_pairs": bool(anti), "overridden": bool(overridden)},
+        # the two figures the stated metric names literally, for this workload (details in parts)
+        "baseline_metrics": {
+            "qgemm_member_tokens_per_s": parts["gemm_member_tokens_per_s"],
+            "qgemm_mfma_frac": parts["gemm_mfma_frac"],
+            "update_replay_gb_per_s": parts["update_gb_per_s"],
+            "update_replay_hbm_frac": parts["update_hbm_frac"],
+        },
         "roofline": roofline,
         "parts": parts,
     }
