@@ -245,14 +245,18 @@ def measure_ceilings(torch, qes, dev):
     this run: Philox words/s and full pair draws/s (four chains per thread, eight waves per SIMD, no
     memory), bf16 and int8 matrix instructions on register operands, a plain streaming copy."""
     out = {}
-    n_threads = 256 * 4 * 8 * 64 * 2          # two full rounds of 8 waves per SIMD
+    # the update kernel's launch shape: many short waves (256 rounds of 8 waves per SIMD, 64 pair draws
+    # per thread), about 16 ms per launch. Two rounds of long-running waves measure 7 % less: whole
+    # SIMDs idle while the last waves finish.
+    n_threads = 256 * 4 * 8 * 64 * 256
     sink = torch.empty(n_threads, dtype=torch.int32, device=dev)
-    iters = 8192                              # tens of milliseconds per launch: clocks settle, the tail is small
+    iters = 64
     ms = time_call(torch, lambda: qes.bench_noise(0, n_threads, iters, 1.0, sink), 3, warm=2)
     out["philox_words_per_s"] = 4.0 * n_threads * iters / (ms * 1e-3)
     ms = time_call(torch, lambda: qes.bench_noise(1, n_threads, iters, 1.0, sink), 3, warm=2)
     out["pair_draws_per_s"] = n_threads * iters / (ms * 1e-3)
     out["draws_per_s"] = 2.0 * out["pair_draws_per_s"]
+    del sink
     n_blocks, m_iters, tiles = 256 * 8, 16384, 8
     msink = torch.empty(n_blocks * 256, dtype=torch.int32, device=dev)
     ms = time_call(torch, lambda: qes.bench_mfma(0, n_blocks, m_iters, msink), 5)
