@@ -336,59 +336,84 @@ struct Gemm {
     // ---- one substep: MFMAs of the fragments of substep s on tile buffer `xbuf`, this wave's half
     // fragment of substep s+1 underneath. PAR is the parity of s: it selects the B-fragment buffer
     // at compile time.
-    template <int PERTURB, bool CLAMP, int PAR>
+    template <int PERTURB, bool CLAMP, int PAR, bool LAST>
     __device__ __forceinline__ void substep(int s, const char *xbuf, char *xbuf_next)
     {
-        const bool has_next = (s + 1) < n_sub;
+        constexpr bool has_next = !LAST;
         if (has_next) issue_tile(s + 1, xbuf_next);   // xbuf_next was last read in substep s-1
         const uint2 raw = raw_next;                   // for substep s+1, fetched during substep s-1
-        if (s + 2 < n_sub) raw_next = load_raw(s + 2);
+        // for substep s+2; past the end the last substep's bytes are fetched again and never used, so
+        // that the substep stays one straight-line block
+        if (has_next) raw_next = load_raw(s + 2 < n_sub ? s + 2 : n_sub - 1);
 
+        // fragments of this wave's (member, token tile) items, member-major (at most 4 items), in
+        // the order the matrix instructions use them
+        constexpr int kSteps = kP * kMy;
         Frag b[kP][kWR];
+        Frag af[kSteps];
 #pragma unroll
-        for (int h = 0; h < kP; ++h)
+        for (int q = 0; q < kSteps; ++q) {
+            const int h = q / kMy, i = q % kMy;
+            if (i == 0) {
 #pragma unroll
-            for (int r = 0; r < kWR; ++r) b[h][r].v = *(const uint4 *)(bfrag + (PAR * kP + h) * kFragBytes + frag_rd[r]);
-        constexpr int kBatch = kMy < 4 ? kMy : 4;   // A fragments in flight at a time
-        constexpr int kSteps = kP * kMy;            // (member, token tile) items of this wave, member-major
-        Frag af[kBatch];
-        auto read_batch = [&](int q0) {
-#pragma unroll
-            for (int q = 0; q < kBatch; ++q) {
-                const int h = (q0 + q) / kMy, i = (q0 + q) % kMy;
-                if (kMT % kWM == 0 || wm + i * kWM < kMT)
-                    af[q].v = *(const uint4 *)(xbuf + h * kTileBytes + a_off + i * kWM * 16 * kRowBytes);
+                for (int r = 0; r < kWR; ++r) b[h][r].v = *(const uint4 *)(bfrag + (PAR * kP + h) * kFragBytes + frag_rd[r]);
             }
-        };
-        read_batch(0);
+            if (kMT % kWM == 0 || wm + i * kWM < kMT)
+                af[q].v = *(const uint4 *)(xbuf + h * kTileBytes + a_off + i * kWM * 16 * kRowBytes);
+        }
 
         // half fragment of the next substep; a new scale group may start there (bf16 modes)
         bool new_group = false;
         if (has_next) {
             if (!kI8) {
-                if (--subs_to_group_end == 0) {
-                    subs_to_group_end = subs_per_group;
-                    ++group;
-                    new_group = true;
-                    job_zero = ((job_scale_next & 0x7FFFu) == 0);
-                }
+                new_group = (--subs_to_group_end == 0);   // wave-uniform selects, no branch
+                subs_to_group_end = new_group ? subs_per_group : subs_to_group_end;
+                group += new_group ? 1 : 0;
+                job_zero = new_group ? ((job_scale_next & 0x7FFFu) == 0) : job_zero;
             }
             publish(1 - PAR, make_half<PERTURB, CLAMP>(s + 1, raw, job_zero));
         }
 
 #pragma unroll
-        for (int q0 = 0; q0 < kSteps; q0 += kBatch) {
-            if (q0 > 0) read_batch(q0);
+        for (int q = 0; q < kSteps; ++q) {
+            const int h = q / kMy, i = q % kMy;
+            if (kMT % kWM != 0 && wm + i * kWM >= kMT) continue;
 #pragma unroll
-            for (int q = 0; q < kBatch; ++q) {
-                const int h = (q0 + q) / kMy, i = (q0 + q) % kMy;
-                if (kMT % kWM != 0 && wm + i * kWM >= kMT) continue;
+            for (int r = 0; r < kWR; ++r) {
+                if constexpr (kI8)
+                    acc[h][i][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[q].i8, b[h][r].i8, acc[h][i][r], 0, 0, 0);
+                else
+                    acc[h][i][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[q].bf, b[h][r].bf, acc[h][i][r], 0, 0, 0);
+            }
+        }
+        if constexpr (has_next) {
+            // Instruction order of the block above: the first part of the noise job, then the LDS
+            // reads of the first two items' fragments, then one matrix instruction after every kGap
+            // vector instructions of the rest of the noise job, each further item's fragments read
+            // two items ahead of their use. So a wave's own vector work runs while the matrix pipe
+            // is busy, instead of all MFMAs queueing up behind the noise, and only the fragments of
+            // three items are held in registers at a time. Accumulation order per accumulator is
+            // unchanged.
+            constexpr int kAhead = kSteps < 2 ? kSteps : 2;
+            constexpr int kMfma = kSteps * kWR;
+            constexpr int kNoiseValu = (H / 2) * (PAIRED ? 140 : 115);
+            // the 8-wave 256-token tile has no registers to spare: there the reads wait for the
+            // first half of the noise job
+            constexpr int kLead = (TM == 256 && !PAIRED) ? kNoiseValu / 2 : 0;
+            constexpr int kGap = (kNoiseValu - kLead - 10) / (kMfma + (kLead == 0 ? 1 : 0));
+            auto reads_of = [](int q) constexpr { return 1 + (q % kMy == 0 ? kWR : 0); };   // A, and B at a member's first item
+            if (kLead > 0) __builtin_amdgcn_sched_group_barrier(0x002, kLead, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, reads_of(0) + (kAhead > 1 ? reads_of(1) : 0), 0);
+#pragma unroll
+            for (int q = 0; q < kSteps; ++q) {
 #pragma unroll
                 for (int r = 0; r < kWR; ++r) {
-                    if constexpr (kI8)
-                        acc[h][i][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[q].i8, b[h][r].i8, acc[h][i][r], 0, 0, 0);
-                    else
-                        acc[h][i][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[q].bf, b[h][r].bf, acc[h][i][r], 0, 0, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, kGap, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+                if (q + kAhead < kSteps) {
+                    if ((q + kAhead) % kMy == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1 + kWR, 0);
+                    else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 }
             }
         }
@@ -448,9 +473,17 @@ struct Gemm {
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
 
-        for (int s = 0; s < n_sub; s += 2) {
-            substep<PERTURB, CLAMP, 0>(s, x0, x1);
-            if (s + 1 < n_sub) substep<PERTURB, CLAMP, 1>(s + 1, x1, x0);
+        // every substep but the last generates the next substep's fragments under its MFMAs
+        int s = 0;
+        for (; s + 2 < n_sub; s += 2) {
+            substep<PERTURB, CLAMP, 0, false>(s, x0, x1);
+            substep<PERTURB, CLAMP, 1, false>(s + 1, x1, x0);
+        }
+        if (s + 1 < n_sub) {
+            substep<PERTURB, CLAMP, 0, false>(s, x0, x1);
+            substep<PERTURB, CLAMP, 1, true>(s + 1, x1, x0);
+        } else {
+            substep<PERTURB, CLAMP, 0, true>(s, x0, x1);
         }
 
 #pragma unroll
@@ -482,7 +515,7 @@ struct Gemm {
 // a block finds its tensor by bisection over the tensors' first slots in the per-XCD queues.
 // Register budget: two workgroups per CU (4 waves per SIMD) also for the largest accumulator sets.
 template <int MODE, int TM, bool PAIRED, bool BATCH>
-__global__ __launch_bounds__(waves_for(TM, PAIRED) * 64, ((TM >= 512 || (PAIRED && TM >= 128)) ? 4 : 1)) void gemm_kernel(const GemmArgs args)
+__global__ __launch_bounds__(waves_for(TM, PAIRED) * 64, ((TM >= 256 || (PAIRED && TM >= 128)) ? 4 : 1)) void gemm_kernel(const GemmArgs args)
 {
     using G = Gemm<MODE, TM, PAIRED>;
     constexpr int kP = G::kP;
