@@ -173,6 +173,11 @@ struct Gemm {
     static constexpr int kInstr = TM / 16;                     // wave instructions per activation tile
     static constexpr int kMyInstr = (kInstr + kWaves - 1) / kWaves;
     static constexpr int H = (kI8 ? 16 : 8) / kParts;          // elements in this wave's part of a fragment
+    // One straight-line block per substep with the matrix instructions spread over the noise job,
+    // except where 32 accumulator registers per lane leave no room for the longer fragment lifetimes
+    // (the 8-wave 256-token tile, a pair of members at 128 tokens): those would need more than 128
+    // registers (one workgroup per CU) or spill.
+    static constexpr bool kStraight = !(TM == 256 && !PAIRED) && !(TM == 128 && PAIRED);
     static constexpr int kWBytesPerSub = (MODE == kBf16W4) ? 16 : (MODE == kBf16W8 ? 32 : 64);   // weight bytes per row and substep
     using Acc = typename std::conditional<kI8, i32x4, f32x4>::type;
 
@@ -339,28 +344,44 @@ struct Gemm {
     template <int PERTURB, bool CLAMP, int PAR, bool LAST>
     __device__ __forceinline__ void substep(int s, const char *xbuf, char *xbuf_next)
     {
-        constexpr bool has_next = !LAST;
+        // kStraight: whether a next substep exists is known at compile time (LAST) and the substep
+        // is one straight-line block. Otherwise it is tested at run time (LAST is false throughout).
+        const bool has_next = kStraight ? !LAST : (s + 1) < n_sub;
         if (has_next) issue_tile(s + 1, xbuf_next);   // xbuf_next was last read in substep s-1
         const uint2 raw = raw_next;                   // for substep s+1, fetched during substep s-1
-        // for substep s+2; past the end the last substep's bytes are fetched again and never used, so
-        // that the substep stays one straight-line block
-        if (has_next) raw_next = load_raw(s + 2 < n_sub ? s + 2 : n_sub - 1);
-
-        // fragments of this wave's (member, token tile) items, member-major (at most 4 items), in
-        // the order the matrix instructions use them
-        constexpr int kSteps = kP * kMy;
-        Frag b[kP][kWR];
-        Frag af[kSteps];
-#pragma unroll
-        for (int q = 0; q < kSteps; ++q) {
-            const int h = q / kMy, i = q % kMy;
-            if (i == 0) {
-#pragma unroll
-                for (int r = 0; r < kWR; ++r) b[h][r].v = *(const uint4 *)(bfrag + (PAR * kP + h) * kFragBytes + frag_rd[r]);
-            }
-            if (kMT % kWM == 0 || wm + i * kWM < kMT)
-                af[q].v = *(const uint4 *)(xbuf + h * kTileBytes + a_off + i * kWM * 16 * kRowBytes);
+        if (kStraight) {
+            // for substep s+2; past the end the last substep's bytes are fetched again and never used
+            if (has_next) raw_next = load_raw(s + 2 < n_sub ? s + 2 : n_sub - 1);
+        } else if (s + 2 < n_sub) {
+            raw_next = load_raw(s + 2);
         }
+
+        // Fragments of this wave's (member, token tile) items, member-major (at most 4 items). In
+        // the straight-line form all of them are requested here, in the order the matrix
+        // instructions use them (the scheduling groups below place the reads); otherwise the B
+        // fragments and one batch of A fragments, the next batch after the first one's MFMAs.
+        constexpr int kSteps = kP * kMy;
+        constexpr int kBatch = kStraight ? kSteps : (kMy < 4 ? kMy : 4);
+        Frag b[kP][kWR];
+        Frag af[kBatch];
+        auto read_b = [&](int h) {
+#pragma unroll
+            for (int r = 0; r < kWR; ++r) b[h][r].v = *(const uint4 *)(bfrag + (PAR * kP + h) * kFragBytes + frag_rd[r]);
+        };
+        auto read_batch = [&](int q0) {
+#pragma unroll
+            for (int q = 0; q < kBatch; ++q) {
+                const int h = (q0 + q) / kMy, i = (q0 + q) % kMy;
+                if (kStraight && i == 0) read_b(h);
+                if (kMT % kWM == 0 || wm + i * kWM < kMT)
+                    af[q].v = *(const uint4 *)(xbuf + h * kTileBytes + a_off + i * kWM * 16 * kRowBytes);
+            }
+        };
+        if (!kStraight) {
+#pragma unroll
+            for (int h = 0; h < kP; ++h) read_b(h);
+        }
+        read_batch(0);
 
         // half fragment of the next substep; a new scale group may start there (bf16 modes)
         bool new_group = false;
@@ -375,18 +396,22 @@ struct Gemm {
         }
 
 #pragma unroll
-        for (int q = 0; q < kSteps; ++q) {
-            const int h = q / kMy, i = q % kMy;
-            if (kMT % kWM != 0 && wm + i * kWM >= kMT) continue;
+        for (int q0 = 0; q0 < kSteps; q0 += kBatch) {
+            if (q0 > 0) read_batch(q0);
 #pragma unroll
-            for (int r = 0; r < kWR; ++r) {
-                if constexpr (kI8)
-                    acc[h][i][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[q].i8, b[h][r].i8, acc[h][i][r], 0, 0, 0);
-                else
-                    acc[h][i][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[q].bf, b[h][r].bf, acc[h][i][r], 0, 0, 0);
+            for (int q = 0; q < kBatch; ++q) {
+                const int h = (q0 + q) / kMy, i = (q0 + q) % kMy;
+                if (kMT % kWM != 0 && wm + i * kWM >= kMT) continue;
+#pragma unroll
+                for (int r = 0; r < kWR; ++r) {
+                    if constexpr (kI8)
+                        acc[h][i][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[q].i8, b[h][r].i8, acc[h][i][r], 0, 0, 0);
+                    else
+                        acc[h][i][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[q].bf, b[h][r].bf, acc[h][i][r], 0, 0, 0);
+                }
             }
         }
-        if constexpr (has_next) {
+        if constexpr (kStraight && !LAST) {
             // Instruction order of the block above: the first part of the noise job, then the LDS
             // reads of the first two items' fragments, then one matrix instruction after every kGap
             // vector instructions of the rest of the noise job, each further item's fragments read
@@ -394,15 +419,11 @@ struct Gemm {
             // is busy, instead of all MFMAs queueing up behind the noise, and only the fragments of
             // three items are held in registers at a time. Accumulation order per accumulator is
             // unchanged.
-            constexpr int kAhead = kSteps < 2 ? kSteps : 2;
+            constexpr int kAhead = (kSteps < 2 || (PAIRED && TM == 256)) ? 1 : 2;   // the paired 256-token tile has no registers for two
             constexpr int kMfma = kSteps * kWR;
             constexpr int kNoiseValu = (H / 2) * (PAIRED ? 140 : 115);
-            // the 8-wave 256-token tile has no registers to spare: there the reads wait for the
-            // first half of the noise job
-            constexpr int kLead = (TM == 256 && !PAIRED) ? kNoiseValu / 2 : 0;
-            constexpr int kGap = (kNoiseValu - kLead - 10) / (kMfma + (kLead == 0 ? 1 : 0));
+            constexpr int kGap = (kNoiseValu - 10) / (kMfma + 1);
             auto reads_of = [](int q) constexpr { return 1 + (q % kMy == 0 ? kWR : 0); };   // A, and B at a member's first item
-            if (kLead > 0) __builtin_amdgcn_sched_group_barrier(0x002, kLead, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, reads_of(0) + (kAhead > 1 ? reads_of(1) : 0), 0);
 #pragma unroll
             for (int q = 0; q < kSteps; ++q) {
@@ -473,17 +494,24 @@ struct Gemm {
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
 
-        // every substep but the last generates the next substep's fragments under its MFMAs
-        int s = 0;
-        for (; s + 2 < n_sub; s += 2) {
-            substep<PERTURB, CLAMP, 0, false>(s, x0, x1);
-            substep<PERTURB, CLAMP, 1, false>(s + 1, x1, x0);
-        }
-        if (s + 1 < n_sub) {
-            substep<PERTURB, CLAMP, 0, false>(s, x0, x1);
-            substep<PERTURB, CLAMP, 1, true>(s + 1, x1, x0);
+        if constexpr (kStraight) {
+            // every substep but the last generates the next substep's fragments under its MFMAs
+            int s = 0;
+            for (; s + 2 < n_sub; s += 2) {
+                substep<PERTURB, CLAMP, 0, false>(s, x0, x1);
+                substep<PERTURB, CLAMP, 1, false>(s + 1, x1, x0);
+            }
+            if (s + 1 < n_sub) {
+                substep<PERTURB, CLAMP, 0, false>(s, x0, x1);
+                substep<PERTURB, CLAMP, 1, true>(s + 1, x1, x0);
+            } else {
+                substep<PERTURB, CLAMP, 0, true>(s, x0, x1);
+            }
         } else {
-            substep<PERTURB, CLAMP, 0, true>(s, x0, x1);
+            for (int s = 0; s < n_sub; s += 2) {
+                substep<PERTURB, CLAMP, 0, false>(s, x0, x1);
+                if (s + 1 < n_sub) substep<PERTURB, CLAMP, 1, false>(s + 1, x1, x0);
+            }
         }
 
 #pragma unroll
@@ -515,7 +543,7 @@ struct Gemm {
 // a block finds its tensor by bisection over the tensors' first slots in the per-XCD queues.
 // Register budget: two workgroups per CU (4 waves per SIMD) also for the largest accumulator sets.
 template <int MODE, int TM, bool PAIRED, bool BATCH>
-__global__ __launch_bounds__(waves_for(TM, PAIRED) * 64, ((TM >= 256 || (PAIRED && TM >= 128)) ? 4 : 1)) void gemm_kernel(const GemmArgs args)
+__global__ __launch_bounds__(waves_for(TM, PAIRED) * 64, ((TM >= 512 || (PAIRED && TM >= 128)) ? 4 : 1)) void gemm_kernel(const GemmArgs args)
 {
     using G = Gemm<MODE, TM, PAIRED>;
     constexpr int kP = G::kP;
