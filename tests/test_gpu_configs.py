@@ -235,7 +235,7 @@ def test_config_3_layer_0_updated_in_full(env):
 
 
 @pytest.mark.skipif(os.environ.get("QES_LONG_TESTS") != "1",
-                    reason="five minutes of oracle time: run with QES_LONG_TESTS=1")
+                    reason="five minutes of oracle time: run with QES_LONG_TESTS=1 (and -s to see its progress lines)")
 def test_config_5_layer_0_in_full(env):
     """Every output and every element of the headline configuration's first layer (seven tensors,
     218 M parameters, N=32, T=128, K=32): the batched GEMM against the oracle on all columns, all
