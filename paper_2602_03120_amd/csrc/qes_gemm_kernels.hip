@@ -28,7 +28,9 @@
 // into LDS (global_load_lds_dwordx4, no registers) while substep s is consumed; it is
 // double-buffered in two separate LDS arrays (so the compiler knows reads of one never wait for
 // loads into the other) and XOR-swizzled so the b128 fragment reads are conflict-free without
-// padding. One workgroup barrier per substep.
+// padding. One workgroup barrier per substep. Where registers allow, a substep is one straight-line
+// block and scheduling groups spread its matrix instructions over the noise job, so that a wave's
+// vector work continues while the matrix pipe runs.
 //
 // Group scales. The accumulators are kept in units of the current group's scale: at a group
 // boundary they are multiplied by s_old/s_new (one multiply per accumulator) and the integers
