@@ -147,7 +147,7 @@ def test_update_argument_errors(env):
 def test_many_calls_with_changing_record_sizes(env):
     """Back-to-back updates without host synchronisation whose (seed, fitness) record blocks shrink
     and grow (4 members without history up to 512 members with 64 generations): the library's
-    staging slots are reused and regrown underneath; the final weights are the oracle's."""
+    fixed staging slots are reused underneath; the final weights are the oracle's."""
     torch, qes, u, oracle = env["torch"], env["qes"], env["u"], env["oracle"]
     qw, _, qmin, qmax = wl.random_tensor(321, 64, 128, 4, 0)
     ot = oracle.Tensor(qw, None, 64, 128, 4, 0, qmin, qmax, 8)
