@@ -177,9 +177,9 @@ struct Gemm {
     static constexpr int H = (kI8 ? 16 : 8) / kParts;          // elements in this wave's part of a fragment
     // One straight-line block per substep with the matrix instructions spread over the noise job,
     // except where 32 accumulator registers per lane leave no room for the longer fragment lifetimes
-    // (the 8-wave 256-token tile, a pair of members at 128 tokens): those would need more than 128
-    // registers (one workgroup per CU) or spill.
-    static constexpr bool kStraight = !(TM == 256 && !PAIRED) && !(TM == 128 && PAIRED);
+    // (a pair of members at 128 tokens, the 8-wave 256-token tile with int8 operands): those would
+    // need more than 128 registers (one workgroup per CU) or spill.
+    static constexpr bool kStraight = !(TM == 128 && PAIRED) && !(TM == 256 && !PAIRED && kI8);
     static constexpr int kWBytesPerSub = (MODE == kBf16W4) ? 16 : (MODE == kBf16W8 ? 32 : 64);   // weight bytes per row and substep
     using Acc = typename std::conditional<kI8, i32x4, f32x4>::type;
 
@@ -421,7 +421,7 @@ struct Gemm {
             // is busy, instead of all MFMAs queueing up behind the noise, and only the fragments of
             // three items are held in registers at a time. Accumulation order per accumulator is
             // unchanged.
-            constexpr int kAhead = (kSteps < 2 || (PAIRED && TM == 256)) ? 1 : 2;   // the paired 256-token tile has no registers for two
+            constexpr int kAhead = (kSteps < 2 || TM == 256) ? 1 : 2;   // the 256-token tiles have no registers for two
             constexpr int kMfma = kSteps * kWR;
             constexpr int kNoiseValu = (H / 2) * (PAIRED ? 140 : 115);
             constexpr int kGap = (kNoiseValu - 10) / (kMfma + 1);
