@@ -543,9 +543,11 @@ struct Gemm {
 
 // BATCH: one launch covers several tensors (a layer's linears: same members, same token count);
 // a block finds its tensor by bisection over the tensors' first slots in the per-XCD queues.
-// Register budget: two workgroups per CU (4 waves per SIMD) also for the largest accumulator sets.
+// Register budget: two workgroups per CU (4 waves per SIMD) also for the largest accumulator sets;
+// three (6 waves per SIMD, 80 registers) for one member at up to 64 tokens, where a few values that
+// only the prologue and the epilogue use go to scratch memory (none inside the substep loop).
 template <int MODE, int TM, bool PAIRED, bool BATCH>
-__global__ __launch_bounds__(waves_for(TM, PAIRED) * 64, ((TM >= 512 || (PAIRED && TM >= 128)) ? 4 : 1)) void gemm_kernel(const GemmArgs args)
+__global__ __launch_bounds__(waves_for(TM, PAIRED) * 64, ((TM >= 512 || (PAIRED && TM >= 128)) ? 4 : ((TM <= 64 && !PAIRED) ? 6 : 1))) void gemm_kernel(const GemmArgs args)
 {
     using G = Gemm<MODE, TM, PAIRED>;
     constexpr int kP = G::kP;
